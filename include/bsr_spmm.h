@@ -1,0 +1,142 @@
+/*
+ * bsr_spmm -- block-sparse times dense product for AMD MI355X (gfx950).
+ *
+ *     Y = X * W^T        X dense (m, k), W block-sparse (n, k) in BSR, Y dense (m, n)
+ *
+ * The operation and the storage format are those of the paper's Background
+ * section (the three arrays block_data / block_indices / index_pointer, W kept
+ * as (n, k) so that a block-row of W produces a run of consecutive columns of
+ * Y) and of the unnumbered equation in its Approaches section (X W_B^T = Y
+ * with b_r | n and b_c | k):
+ *
+ *     block_data[p][a][c] = W[r*bs_r + a][block_indices[p]*bs_c + c]
+ *         for p in [index_pointer[r], index_pointer[r+1])
+ *     Y[i][r*bs_r + a]    = sum_p sum_c X[i][block_indices[p]*bs_c + c] * block_data[p][a][c]
+ *
+ * Conventions for every entry point
+ *   - plain C ABI; every function returns a bsr_status, never throws or aborts;
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are GPU
+ *     memory of the current HIP device; the library never allocates or frees
+ *     device memory (the caller does, e.g. with PyTorch) and never takes
+ *     ownership of a caller's buffer;
+ *   - dense matrices are row-major and contiguous; index arrays are int32;
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream);
+ *     device work is queued on it and the call returns without waiting.
+ */
+#ifndef BSR_SPMM_H
+#define BSR_SPMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Element types of X, block_data and Y.  Accumulation is always fp32. */
+typedef enum { BSR_F32 = 0, BSR_F16 = 1, BSR_BF16 = 2 } bsr_dtype;
+
+typedef enum {
+    BSR_OK = 0,
+    BSR_ERR_NULL = 1,        /* a required pointer is NULL */
+    BSR_ERR_SHAPE = 2,       /* negative size, bs_r <= 0, bs_c <= 0, bs_r !| n, bs_c !| k (Approaches: b_r | n, b_c | k),
+                                or a size that does not fit the int32 index arithmetic */
+    BSR_ERR_INDPTR = 3,      /* index_pointer[0] != 0, decreasing, or last entry != nnzb */
+    BSR_ERR_INDEX = 4,       /* a block_indices entry outside [0, k/bs_c) */
+    BSR_ERR_DTYPE = 5,       /* unknown dtype, or y_dtype neither the input type nor BSR_F32 */
+    BSR_ERR_ALIGN = 6,       /* a device pointer is not 16-byte aligned */
+    BSR_ERR_WORKSPACE = 7,   /* workspace smaller than bsr_workspace_size() reports */
+    BSR_ERR_HIP = 8,         /* a HIP runtime call failed (launch, copy) */
+    BSR_ERR_UNSUPPORTED = 9  /* the requested kernel path cannot handle this block shape */
+} bsr_status;
+
+/* Which kernel family bsr_spmm_ex() uses. */
+typedef enum {
+    BSR_PATH_AUTO = 0,   /* the library's choice for this matrix and m */
+    BSR_PATH_WAVE = 1,   /* wavefront-reduction kernels: lanes split the reduction inside and across the
+                            stored blocks of a block-row, cross-lane sum at the end (the paper's
+                            "parallelize within blocks" + "aggregate partial results", Sections 4.4.2-4.4.3);
+                            any block shape */
+    BSR_PATH_MFMA = 2    /* matrix-core kernels: one workgroup owns an (m-tile, block-row) tile of Y and walks
+                            the stored blocks of the block-row (the tile-per-thread-block design of the paper's
+                            "Utilizing shared memory" section, with run-time indices); block shapes listed at
+                            bsr_spmm_ex() */
+} bsr_path;
+
+typedef struct bsr_matrix bsr_matrix;   /* opaque handle: shape, device pointers (not owned), plan */
+
+/*
+ * Structural check of a BSR pattern (Background: the three arrays).  HOST pointers.
+ *   n, k        rows / columns of W;   bs_r, bs_c  block shape (bs_r | n, bs_c | k)
+ *   nnzb        number of stored blocks
+ *   index_pointer_host  n/bs_r + 1 entries: starts at 0, non-decreasing, ends at nnzb
+ *   block_indices_host  nnzb entries in [0, k/bs_c); any order inside a block-row, duplicates allowed
+ *                       (duplicates are summed, as the definition sums over stored blocks)
+ * Returns BSR_OK or the first problem found (NULL, SHAPE, INDPTR, INDEX in that order).
+ */
+bsr_status bsr_validate(int64_t n, int64_t k, int32_t bs_r, int32_t bs_c, int64_t nnzb,
+                        const int32_t* index_pointer_host, const int32_t* block_indices_host);
+
+/*
+ * Bytes of DEVICE workspace bsr_create() needs for its plan (block-row order and work lists).
+ * Always > 0 and a multiple of 256.  Errors: NULL, SHAPE.
+ */
+bsr_status bsr_workspace_size(int64_t n, int64_t k, int32_t bs_r, int32_t bs_c, int64_t nnzb,
+                              size_t* bytes);
+
+/*
+ * Build a handle for W.  Validates the pattern (as bsr_validate), bins the block-rows by
+ * their number of stored blocks and orders them longest first (the paper's Discussion: rows
+ * with very different block counts make equal-sized work units diverge), and copies that
+ * plan into `workspace_dev` on `hip_stream` (asynchronous; the host staging copy is owned by
+ * the handle).
+ *   block_data_dev     DEVICE, nnzb*bs_r*bs_c elements of `dtype`, [nnzb][bs_r][bs_c] row-major
+ *   block_indices_dev  DEVICE, nnzb int32          index_pointer_dev  DEVICE, n/bs_r+1 int32
+ *   block_indices_host / index_pointer_host        HOST copies of the same two arrays, read during
+ *                                                  this call only
+ *   workspace_dev      DEVICE, at least bsr_workspace_size() bytes, 16-byte aligned
+ * The four device buffers stay owned by the caller and must outlive the handle; their contents
+ * (block values included) may change between products as long as the pattern does not.
+ * nnzb == 0 is valid (Y becomes all zeros); then block_data_dev / block_indices_* may be NULL.
+ * On error *out is set to NULL.
+ */
+bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int32_t bs_c, int64_t nnzb,
+                      bsr_dtype dtype, const void* block_data_dev,
+                      const int32_t* block_indices_dev, const int32_t* index_pointer_dev,
+                      const int32_t* block_indices_host, const int32_t* index_pointer_host,
+                      void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* Frees the handle's host memory only.  NULL is accepted. */
+void bsr_destroy(bsr_matrix* W);
+
+/*
+ * Y[m][n] = X[m][k] * W^T  (Approaches, the equation; overwrite, not accumulate).
+ *   X_dev   DEVICE, m*k elements of W's dtype, row-major      Y_dev  DEVICE, m*n elements of y_dtype
+ *   y_dtype W's dtype or BSR_F32; the fp32 accumulator is rounded to nearest-even on store
+ *   m       any value >= 0 (m == 0 returns BSR_OK without device work)
+ * Every element of Y is written; columns of an empty block-row are exact zeros.  Asynchronous on
+ * `hip_stream`; no hidden synchronisation; safe to call concurrently on one handle.
+ * Errors: NULL, SHAPE (m < 0 or m*max(k,n) >= 2^31), DTYPE, ALIGN, HIP.
+ */
+bsr_status bsr_spmm(const bsr_matrix* W, int64_t m, const void* X_dev, void* Y_dev,
+                    bsr_dtype y_dtype, void* hip_stream);
+
+/*
+ * As bsr_spmm() with the kernel family fixed.  BSR_PATH_MFMA needs bs_r in {16, 32, 64},
+ * bs_c a multiple of 16 up to 128 (16-bit types) or of 8 up to 64 (fp32), or the thin shape
+ * bs_c == 1 with bs_r == 16 and fp32; otherwise BSR_ERR_UNSUPPORTED.  BSR_PATH_WAVE takes
+ * any shape.
+ */
+bsr_status bsr_spmm_ex(const bsr_matrix* W, int64_t m, const void* X_dev, void* Y_dev,
+                       bsr_dtype y_dtype, bsr_path path, void* hip_stream);
+
+/* The path BSR_PATH_AUTO resolves to for this handle and m (never AUTO).  Errors: NULL. */
+bsr_status bsr_query_path(const bsr_matrix* W, int64_t m, bsr_path* path_out);
+
+/* Static, human-readable text for a status code. */
+const char* bsr_status_string(bsr_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BSR_SPMM_H */

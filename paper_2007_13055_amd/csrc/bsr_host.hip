@@ -1,0 +1,166 @@
+// Host side of libbsr_spmm: structural validation, the block-row plan, handle life cycle and
+// kernel-family dispatch.  Nothing here allocates device memory.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "bsr_internal.h"
+
+namespace {
+
+constexpr int64_t kInt32Limit = (int64_t)1 << 31;
+
+bsr_status check_shape(int64_t n, int64_t k, int32_t bs_r, int32_t bs_c, int64_t nnzb)
+{
+    if (n < 0 || k < 0 || nnzb < 0 || bs_r <= 0 || bs_c <= 0) return BSR_ERR_SHAPE;
+    if (n % bs_r != 0 || k % bs_c != 0) return BSR_ERR_SHAPE;        // b_r | n, b_c | k
+    if (n >= kInt32Limit || k >= kInt32Limit || nnzb >= kInt32Limit) return BSR_ERR_SHAPE;
+    if (nnzb * (int64_t)bs_r * bs_c >= kInt32Limit) return BSR_ERR_SHAPE;   // element offsets are int32
+    if (nnzb > 0 && (n == 0 || k == 0)) return BSR_ERR_SHAPE;
+    return BSR_OK;
+}
+
+size_t plan_bytes(int64_t R, int64_t nnzb)
+{
+    // row order (R int32) plus room for per-row work lists; rounded up to 256 bytes
+    size_t b = 16 * (size_t)(R + nnzb) + 256;
+    return (b + 255) & ~(size_t)255;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+bsr_status bsr_validate(int64_t n, int64_t k, int32_t bs_r, int32_t bs_c, int64_t nnzb,
+                        const int32_t* indptr, const int32_t* indices)
+{
+    if (!indptr) return BSR_ERR_NULL;
+    if (nnzb > 0 && !indices) return BSR_ERR_NULL;
+    bsr_status st = check_shape(n, k, bs_r, bs_c, nnzb);
+    if (st != BSR_OK) return st;
+    const int64_t R = n / bs_r, C = k / bs_c;
+    if (indptr[0] != 0) return BSR_ERR_INDPTR;
+    for (int64_t r = 0; r < R; ++r)
+        if (indptr[r + 1] < indptr[r]) return BSR_ERR_INDPTR;
+    if (indptr[R] != nnzb) return BSR_ERR_INDPTR;
+    for (int64_t p = 0; p < nnzb; ++p)
+        if (indices[p] < 0 || indices[p] >= C) return BSR_ERR_INDEX;
+    return BSR_OK;
+}
+
+bsr_status bsr_workspace_size(int64_t n, int64_t k, int32_t bs_r, int32_t bs_c, int64_t nnzb,
+                              size_t* bytes)
+{
+    if (!bytes) return BSR_ERR_NULL;
+    *bytes = 0;
+    bsr_status st = check_shape(n, k, bs_r, bs_c, nnzb);
+    if (st != BSR_OK) return st;
+    *bytes = plan_bytes(n / bs_r, nnzb);
+    return BSR_OK;
+}
+
+bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int32_t bs_c, int64_t nnzb,
+                      bsr_dtype dtype, const void* block_data_dev,
+                      const int32_t* block_indices_dev, const int32_t* index_pointer_dev,
+                      const int32_t* block_indices_host, const int32_t* index_pointer_host,
+                      void* workspace_dev, size_t workspace_bytes, void* hip_stream)
+{
+    if (!out) return BSR_ERR_NULL;
+    *out = nullptr;
+    if (!index_pointer_dev || !index_pointer_host || !workspace_dev) return BSR_ERR_NULL;
+    if (nnzb > 0 && (!block_data_dev || !block_indices_dev || !block_indices_host)) return BSR_ERR_NULL;
+    if (dtype != BSR_F32 && dtype != BSR_F16 && dtype != BSR_BF16) return BSR_ERR_DTYPE;
+    bsr_status st = bsr_validate(n, k, bs_r, bs_c, nnzb, index_pointer_host, block_indices_host);
+    if (st != BSR_OK) return st;
+    if (!aligned16(block_data_dev) || !aligned16(workspace_dev) ||
+        ((uintptr_t)block_indices_dev & 3u) || ((uintptr_t)index_pointer_dev & 3u))
+        return BSR_ERR_ALIGN;
+    const int64_t R = n / bs_r;
+    if (workspace_bytes < plan_bytes(R, nnzb)) return BSR_ERR_WORKSPACE;
+
+    bsr_matrix* W = new (std::nothrow) bsr_matrix();
+    if (!W) return BSR_ERR_HIP;
+    W->n = n; W->k = k; W->nnzb = nnzb; W->bs_r = bs_r; W->bs_c = bs_c;
+    W->R = (int32_t)R; W->C = (int32_t)(k / bs_c);
+    W->dtype = dtype;
+    W->data = block_data_dev; W->indices = block_indices_dev; W->indptr = index_pointer_dev;
+
+    // ---- plan: block-rows by stored-block count, longest first (stable, so equal rows keep
+    //      their natural order and neighbouring rows stay neighbours in the launch) ----
+    std::vector<int32_t> cnt((size_t)R);
+    for (int64_t r = 0; r < R; ++r) cnt[(size_t)r] = index_pointer_host[r + 1] - index_pointer_host[r];
+    W->staging.resize((size_t)std::max<int64_t>(R, 1));
+    std::iota(W->staging.begin(), W->staging.begin() + R, 0);
+    std::stable_sort(W->staging.begin(), W->staging.begin() + R,
+                     [&](int32_t a, int32_t b) { return cnt[(size_t)a] > cnt[(size_t)b]; });
+    W->max_row_blocks = R ? *std::max_element(cnt.begin(), cnt.end()) : 0;
+    W->empty_rows = (int32_t)std::count(cnt.begin(), cnt.end(), 0);
+    W->mean_row_blocks = R ? (double)nnzb / (double)R : 0.0;
+    W->row_order = static_cast<const int32_t*>(workspace_dev);
+    if (R > 0) {
+        hipError_t e = hipMemcpyAsync(workspace_dev, W->staging.data(), sizeof(int32_t) * (size_t)R,
+                                      hipMemcpyHostToDevice, (hipStream_t)hip_stream);
+        if (e != hipSuccess) { delete W; return BSR_ERR_HIP; }
+    }
+    *out = W;
+    return BSR_OK;
+}
+
+void bsr_destroy(bsr_matrix* W) { delete W; }
+
+bsr_status bsr_query_path(const bsr_matrix* W, int64_t m, bsr_path* path_out)
+{
+    if (!W || !path_out) return BSR_ERR_NULL;
+    // Matrix-core tiles are at least 16 rows of X tall: below that most of a tile is padding and
+    // the wavefront-reduction kernels (the paper's own regime, m <= 8) stream W once instead.
+    *path_out = (mfma_supports(W) && m >= 16) ? BSR_PATH_MFMA : BSR_PATH_WAVE;
+    return BSR_OK;
+}
+
+bsr_status bsr_spmm_ex(const bsr_matrix* W, int64_t m, const void* X_dev, void* Y_dev,
+                       bsr_dtype y_dtype, bsr_path path, void* hip_stream)
+{
+    if (!W) return BSR_ERR_NULL;
+    if (m < 0) return BSR_ERR_SHAPE;
+    if (y_dtype != W->dtype && y_dtype != BSR_F32) return BSR_ERR_DTYPE;
+    if (path != BSR_PATH_AUTO && path != BSR_PATH_WAVE && path != BSR_PATH_MFMA) return BSR_ERR_UNSUPPORTED;
+    if (m == 0 || W->n == 0) return BSR_OK;
+    if (!Y_dev || (W->k > 0 && !X_dev)) return BSR_ERR_NULL;
+    if (m * std::max<int64_t>(W->k, W->n) >= kInt32Limit) return BSR_ERR_SHAPE;
+    if (!aligned16(X_dev) || !aligned16(Y_dev)) return BSR_ERR_ALIGN;
+    if (path == BSR_PATH_AUTO) bsr_query_path(W, m, &path);
+    spmm_args a{W, m, X_dev, Y_dev, y_dtype, (hipStream_t)hip_stream};
+    if (path == BSR_PATH_MFMA) {
+        if (!mfma_supports(W)) return BSR_ERR_UNSUPPORTED;
+        return launch_mfma(a);
+    }
+    return launch_wave(a);
+}
+
+bsr_status bsr_spmm(const bsr_matrix* W, int64_t m, const void* X_dev, void* Y_dev,
+                    bsr_dtype y_dtype, void* hip_stream)
+{
+    return bsr_spmm_ex(W, m, X_dev, Y_dev, y_dtype, BSR_PATH_AUTO, hip_stream);
+}
+
+const char* bsr_status_string(bsr_status s)
+{
+    switch (s) {
+        case BSR_OK: return "ok";
+        case BSR_ERR_NULL: return "a required pointer is NULL";
+        case BSR_ERR_SHAPE: return "bad shape: negative size, block size not dividing n or k, or beyond int32 indexing";
+        case BSR_ERR_INDPTR: return "index_pointer must start at 0, never decrease and end at the block count";
+        case BSR_ERR_INDEX: return "block_indices entry outside [0, k / bs_c)";
+        case BSR_ERR_DTYPE: return "unknown dtype, or output type neither the input type nor fp32";
+        case BSR_ERR_ALIGN: return "device pointer not 16-byte aligned";
+        case BSR_ERR_WORKSPACE: return "workspace smaller than bsr_workspace_size() reports";
+        case BSR_ERR_HIP: return "HIP runtime call failed";
+        case BSR_ERR_UNSUPPORTED: return "requested kernel path does not support this block shape";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,232 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bar: |Y_gpu - Y_oracle| <= tau * sum|x*w| with tau = 1e-5 (fp32 inputs) or 2e-3 (fp16 / bf16 inputs,
+fp32 accumulation); exact zeros where the exact result is zero; bitwise equality for integer-valued
+inputs.  The oracle's double result is never re-rounded to the output type.
+"""
+import numpy as np
+import pytest
+
+import workloads as wl
+from gpu_util import check, gpu_product, to_device
+
+pytestmark = pytest.mark.gpu
+
+WAVE, MFMA = 1, 2
+
+
+def oracle_of(oracle_mod, p, rows=None):
+    return oracle_mod.bsr_spmm(p.X, p.block_data, p.block_indices, p.index_pointer, p.n, rows=rows)
+
+
+# ------------------------------------------------------------------ both paths, many shapes
+SHAPES = [(16, 16), (16, 32), (16, 64), (32, 16), (32, 32), (32, 64), (64, 16), (64, 32), (64, 64)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("bs", SHAPES)
+def test_mfma_path_block_shapes(oracle_mod, dtype, bs):
+    bs_r, bs_c = bs
+    for m in (1, 17, 100, 300):                       # single partial tile ... several tiles + ragged tail
+        p = wl.make_problem("s", m, 6 * bs_c, 5 * bs_r, bs_r, bs_c, dtype, dtype, ("bernoulli", 0.5),
+                            ("normal", 1.0), ("normal", 1.0), 100 + m + bs_r + bs_c)
+        Yo, So = oracle_of(oracle_mod, p)
+        Yg, W = gpu_product(p, path=MFMA)
+        check(Yg, Yo, So, p.tau, f"mfma {dtype} {bs} m={m}", out_dtype=dtype)
+        if dtype != "f32":
+            # fp32 output: the stated bar alone; and the 16-bit output must be exactly the
+            # nearest-even rounding of that fp32 result (same kernel, same summation order)
+            Yg32, _ = gpu_product(p, path=MFMA, y_dtype="f32", W=W)
+            check(Yg32, Yo, So, p.tau, f"mfma {dtype}->f32 {bs} m={m}")
+            assert np.array_equal(wl.round_to_storage(Yg32.astype(np.float32), dtype).astype(np.float64), Yg)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("bs", [(16, 16), (8, 8), (16, 1), (1, 16), (3, 5), (32, 32), (64, 64), (1, 1), (4, 8)])
+def test_wave_path_block_shapes(oracle_mod, dtype, bs):
+    bs_r, bs_c = bs
+    for m in (1, 3, 8, 21):
+        p = wl.make_problem("s", m, 12 * bs_c, 7 * bs_r, bs_r, bs_c, dtype, dtype, ("bernoulli", 0.5),
+                            ("normal", 1.0), ("normal", 1.0), 200 + m + bs_r + bs_c)
+        Yo, So = oracle_of(oracle_mod, p)
+        Yg, W = gpu_product(p, path=WAVE)
+        check(Yg, Yo, So, p.tau, f"wave {dtype} {bs} m={m}", out_dtype=dtype)
+        if dtype != "f32":
+            Yg32, _ = gpu_product(p, path=WAVE, y_dtype="f32", W=W)
+            check(Yg32, Yo, So, p.tau, f"wave {dtype}->f32 {bs} m={m}")
+            assert np.array_equal(wl.round_to_storage(Yg32.astype(np.float32), dtype).astype(np.float64), Yg)
+
+
+# ------------------------------------------------------------------ the five configurations, full size
+@pytest.mark.parametrize("cid", [1, 2, 3, 4])
+def test_config_full_size_auto_path(oracle_mod, cid):
+    p = wl.config(cid)
+    Yo, So = oracle_of(oracle_mod, p)
+    Yg, W = gpu_product(p)
+    check(Yg, Yo, So, p.tau, f"config {cid} auto", out_dtype=p.out_dtype)
+    if p.out_dtype != "f32":
+        # the stated bar alone on the fp32 accumulator; the 16-bit Y is its nearest-even rounding
+        Yg32, _ = gpu_product(p, y_dtype="f32", W=W)
+        check(Yg32, Yo, So, p.tau, f"config {cid} auto, fp32 output")
+        assert np.array_equal(wl.round_to_storage(Yg32.astype(np.float32), p.out_dtype).astype(np.float64), Yg)
+
+
+@pytest.mark.parametrize("cid", [1, 2, 4])
+def test_config_full_size_wave_path(oracle_mod, cid):
+    p = wl.config(cid)
+    Yo, So = oracle_of(oracle_mod, p)
+    Yg, _ = gpu_product(p, path=WAVE)
+    check(Yg, Yo, So, p.tau, f"config {cid} wave")
+
+
+def test_config5_full_size_sampled_rows(oracle_mod):
+    """8192 x 8192 x 8192 fp16: the GPU computes everything, the oracle the sampled rows
+    (tile edges, first / last rows, a seeded random set)."""
+    p = wl.config(5)
+    rng = np.random.default_rng(5)
+    rows = sorted(set([0, 1, 31, 32, 63, 64, 127, 128, 255, 256, 4095, 4096, 8190, 8191]
+                      + rng.integers(0, p.m, size=50).tolist()))
+    Yo, So = oracle_of(oracle_mod, p, rows=rows)
+    Yg, W = gpu_product(p, rows=rows)
+    check(Yg, Yo, So, p.tau, "config 5 sampled rows", out_dtype=p.out_dtype)
+    Yg32, _ = gpu_product(p, rows=rows, y_dtype="f32", W=W)
+    check(Yg32, Yo, So, p.tau, "config 5 sampled rows, fp32 output")
+    assert np.array_equal(wl.round_to_storage(Yg32.astype(np.float32), "f16").astype(np.float64), Yg)
+
+
+# ------------------------------------------------------------------ exact cases
+@pytest.mark.parametrize("path", [WAVE, MFMA])
+@pytest.mark.parametrize("dtype,out", [("f32", "f32"), ("f16", "f32"), ("bf16", "f32"), ("f16", "f16")])
+def test_small_integers_are_bitwise_exact(oracle_mod, path, dtype, out):
+    """|values| <= 4 and short sums: every partial sum is an exactly representable integer, so any
+    summation order must give the oracle's value bit for bit (also after fp16 rounding: |y| < 2048)."""
+    p = wl.small_integer_problem(70, 8 * 16, 6 * 16, 16, 16, 0.5, seed=11, in_dtype=dtype, out_dtype=out,
+                                 lo=-3, hi=3)
+    Yo, So = oracle_of(oracle_mod, p)
+    assert np.abs(Yo).max() < 2048
+    Yg, _ = gpu_product(p, path=path)
+    assert np.array_equal(Yg, Yo)
+
+
+@pytest.mark.parametrize("path", [WAVE, MFMA])
+def test_all_ones_closed_form(path):
+    """X = 1, stored blocks = 1  =>  Y[i, r*bs_r + a] = bs_c * (stored blocks of block-row r)."""
+    bs_r, bs_c, R, C, m = 32, 32, 9, 10, 40
+    rng = np.random.default_rng(1)
+    counts = rng.integers(0, C + 1, size=R)
+    counts[3] = 0
+    ptr, idx = wl.pattern_from_counts(rng, counts, C)
+    p = wl.Problem("ones", m, C * bs_c, R * bs_r, bs_r, bs_c, "f32", "f32", np.ones((m, C * bs_c), np.float32),
+                   np.ones((idx.shape[0], bs_r, bs_c), np.float32), idx, ptr)
+    Yg, _ = gpu_product(p, path=path)
+    assert np.array_equal(Yg, np.tile(np.repeat(counts * bs_c, bs_r).astype(np.float64), (m, 1)))
+
+
+@pytest.mark.parametrize("path", [WAVE, MFMA])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_block_diagonal_identity_returns_x(path, dtype):
+    bs, R, m = 16, 6, 37
+    X = wl.round_to_storage(np.random.default_rng(3).normal(size=(m, R * bs)).astype(np.float32), dtype)
+    p = wl.Problem("eye", m, R * bs, R * bs, bs, bs, dtype, dtype, X,
+                   np.tile(np.eye(bs, dtype=np.float32), (R, 1, 1)), np.arange(R, dtype=np.int32),
+                   np.arange(R + 1, dtype=np.int32))
+    Yg, _ = gpu_product(p, path=path)
+    assert np.array_equal(Yg, X.astype(np.float64))
+
+
+@pytest.mark.parametrize("path", [WAVE, MFMA])
+def test_single_one_selects_a_column(path):
+    bs_r, bs_c, R, C, m = 16, 32, 4, 5, 19
+    X = np.random.default_rng(2).normal(size=(m, C * bs_c)).astype(np.float32)
+    for (r, cb, a, c) in [(0, 0, 0, 0), (2, 4, bs_r - 1, bs_c - 1), (3, 1, 7, 13)]:
+        blk = np.zeros((1, bs_r, bs_c), np.float32)
+        blk[0, a, c] = 1.0
+        ptr = np.zeros(R + 1, np.int32)
+        ptr[r + 1:] = 1
+        p = wl.Problem("sel", m, C * bs_c, R * bs_r, bs_r, bs_c, "f32", "f32", X, blk,
+                       np.array([cb], np.int32), ptr)
+        Yg, _ = gpu_product(p, path=path)
+        expect = np.zeros((m, R * bs_r))
+        expect[:, r * bs_r + a] = X[:, cb * bs_c + c]
+        assert np.array_equal(Yg, expect)
+
+
+@pytest.mark.parametrize("path", [WAVE, MFMA])
+def test_empty_rows_overwrite_with_exact_zero(oracle_mod, path):
+    """Y is pre-filled with NaN: every element must be overwritten, empty block-rows with +0."""
+    m, bs = 45, 16
+    for counts in ([0, 3, 0, 0, 2, 0], [0] * 6, [4, 0, 0, 0, 0, 1]):
+        p = wl.make_problem("e", m, 8 * bs, 6 * bs, bs, bs, "f32", "f32", ("counts", np.array(counts)),
+                            ("normal", 1.0), ("normal", 1.0), 5)
+        Yo, So = oracle_of(oracle_mod, p)
+        Yg, _ = gpu_product(p, path=path)
+        check(Yg, Yo, So, p.tau, f"empty rows {counts}")
+        for r, cnt in enumerate(counts):
+            if cnt == 0:
+                assert np.all(Yg[:, r * bs:(r + 1) * bs] == 0)
+
+
+@pytest.mark.parametrize("path", [WAVE, MFMA])
+def test_unsorted_and_duplicate_blocks(oracle_mod, path):
+    p = wl.small_integer_problem(33, 8 * 16, 5 * 16, 16, 16, 0.6, seed=3)
+    rng = np.random.default_rng(9)
+    data, idx = p.block_data.copy(), p.block_indices.copy()
+    for r in range(p.n // p.bs_r):
+        a, b = p.index_pointer[r], p.index_pointer[r + 1]
+        perm = rng.permutation(b - a) + a
+        data[a:b], idx[a:b] = p.block_data[perm], p.block_indices[perm]
+    q = wl.Problem("perm", p.m, p.k, p.n, 16, 16, "f32", "f32", p.X, data, idx, p.index_pointer)
+    Y0, _ = gpu_product(p, path=path)
+    Y1, _ = gpu_product(q, path=path)
+    assert np.array_equal(Y0, Y1)                     # integer-valued: exact under permutation
+    # duplicates: the same block stored twice counts twice
+    d2 = np.concatenate([p.block_data[:1], p.block_data])
+    i2 = np.concatenate([p.block_indices[:1], p.block_indices])
+    ptr2 = p.index_pointer.copy()
+    ptr2[1:] += 1
+    dup = wl.Problem("dup", p.m, p.k, p.n, 16, 16, "f32", "f32", p.X, d2, i2, ptr2)
+    Yo, So = oracle_of(oracle_mod, dup)
+    Yg, _ = gpu_product(dup, path=path)
+    assert np.array_equal(Yg, Yo)
+
+
+# ------------------------------------------------------------------ paper grid (m = 1, 8)
+@pytest.mark.parametrize("cell", [(1, 128, 768, 8, 0.8), (8, 128, 768, 16, 0.95), (8, 128, 768, 32, 0.85),
+                                  (1, 1024, 1024, 16, 0.85), (8, 1024, 1024, 8, 0.95),
+                                  (8, 1024, 1024, 32, 0.8)])
+def test_paper_grid_cells(oracle_mod, cell):
+    p = wl.paper_grid_problem(*cell)
+    Yo, So = oracle_of(oracle_mod, p)
+    Yg, _ = gpu_product(p)
+    check(Yg, Yo, So, p.tau, f"paper grid {cell}")
+
+
+# ------------------------------------------------------------------ boundary behaviour
+def test_degenerate_sizes_and_errors():
+    import torch
+    import paper_2007_13055_amd as lib
+    W = lib.bsr_create(32, 32, np.zeros((0, 16, 16), np.float32), [], [0, 0, 0])
+    X = torch.ones((5, 32), device="cuda")
+    Y = lib.bsr_spmm(W, X)
+    torch.cuda.synchronize()
+    assert torch.all(Y == 0)
+    Y0 = lib.bsr_spmm(W, torch.ones((0, 32), device="cuda"))         # m = 0: no device work
+    assert tuple(Y0.shape) == (0, 32)
+    p = wl.make_problem("t", 4, 15, 20, 5, 3, "f32", "f32", ("bernoulli", 0.5), ("normal", 1), ("normal", 1), 1)
+    Wodd = lib.bsr_create(p.n, p.k, p.block_data, p.block_indices, p.index_pointer)
+    assert lib.bsr_query_path(Wodd, 64) == WAVE
+    with pytest.raises(lib.BsrError) as e:
+        lib.bsr_spmm_ex(Wodd, to_device(p.X, "f32"), path=MFMA)
+    assert e.value.status == 9
+    with pytest.raises(lib.BsrError) as e:                           # misaligned X
+        buf = torch.zeros(4 * 15 + 1, device="cuda")
+        lib.bsr_spmm(Wodd, buf[1:].view(4, 15))
+    assert e.value.status == 6
+
+
+def test_repeat_calls_are_bitwise_identical(oracle_mod):
+    """No atomics in the default plan: two runs must agree bit for bit (catches races)."""
+    p = wl.config(2)
+    Y1, W = gpu_product(p)
+    Y2, _ = gpu_product(p, W=W)
+    assert np.array_equal(Y1, Y2)
