@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of bsr_spmm on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-all-configs] [--no-cpu]
+
+A step is one whole product Y = X * W^T (one bsr_spmm call) on the headline workload, the
+"Transformer FFN weight" configuration (fp32, m=128, k=n=3072, 32x32 blocks, density 0.10), with
+X, W and Y already resident in HBM.  Prints ONE JSON line: effective TFLOP/s
+(2*m*nnzb*bs_r*bs_c per call), the roofline object of the product kernel, the CPU oracle timed on
+this machine's host cores, and a per-configuration table for the other four workloads.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# Published MI355X peaks used as roofline ceilings.
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_TFLOPS = {"f32": 157.3, "f16": 2500.0, "bf16": 2500.0}
+HEADLINE = 2
+
+
+def _upload(p):
+    import torch
+    import paper_2007_13055_amd as lib
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+    W = lib.bsr_create(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype=p.in_dtype)
+    X = torch.from_numpy(p.X).to("cuda", dtype=tdt[p.in_dtype])
+    Y = torch.empty((p.m, p.n), dtype=tdt[p.out_dtype], device="cuda")
+    return W, X, Y
+
+
+def _time_steps(fn, steps, warmup, graph_chunk):
+    """Time exactly `steps` calls of fn() on torch's current stream.
+
+    Returns (wall seconds over the region, HIP-event seconds over the same region, mode).  With
+    graph_chunk > 0 the calls are captured once into a HIP graph of graph_chunk launches and the
+    region replays it steps/graph_chunk times (same kernels, same work, host launch cost amortised).
+    """
+    import torch
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    run, mode = None, "eager"
+    if graph_chunk > 0 and steps % graph_chunk == 0:
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(stream)
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                fn()
+                torch.cuda.synchronize()
+                with torch.cuda.graph(g, stream=side):
+                    for _ in range(graph_chunk):
+                        fn()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            reps = steps // graph_chunk
+
+            def run():
+                for _ in range(reps):
+                    g.replay()
+            mode = f"hipgraph x{graph_chunk}"
+        except Exception as e:                       # capture refused: fall back to plain launches
+            sys.stderr.write(f"[bench] graph capture unavailable ({e}); timing eager launches\n")
+            run = None
+    if run is None:
+        def run():
+            for _ in range(steps):
+                fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record(stream)
+    run()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, e0.elapsed_time(e1) * 1e-3, mode
+
+
+def _roofline(p, sec_per_launch):
+    """Both ceilings for one launch; the binding one is the slower of the two at peak."""
+    t_hbm = p.algorithmic_bytes() / (PEAK_HBM_GBS * 1e9)
+    t_mfma = p.flops / (PEAK_MFMA_TFLOPS[p.in_dtype] * 1e12)
+    if t_mfma >= t_hbm:
+        ach = p.flops / sec_per_launch / 1e12
+        return {"bound": "mfma", "achieved": ach, "peak": PEAK_MFMA_TFLOPS[p.in_dtype], "unit": "TFLOP/s",
+                "frac": ach / PEAK_MFMA_TFLOPS[p.in_dtype], "traffic": None}
+    ach = p.algorithmic_bytes() / sec_per_launch / 1e9
+    return {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
+            "traffic": None}
+
+
+def _bench_config(cid, steps, warmup, graph_chunk):
+    import workloads as wl
+    import paper_2007_13055_amd as lib
+    p = wl.config(cid)
+    W, X, Y = _upload(p)
+    fn = lambda: lib.bsr_spmm(W, X, Y)
+    wall, ev, mode = _time_steps(fn, steps, warmup, graph_chunk)
+    eager_wall, _, _ = _time_steps(fn, steps, 0, 0)
+    return p, W, {"wall_s": wall, "event_s": ev, "mode": mode, "eager_wall_s": eager_wall,
+                  "path": {1: "wave", 2: "mfma"}[lib.bsr_query_path(W, p.m)]}
+
+
+def _launch_floor(steps, graph_chunk):
+    """Average time of a do-nothing kernel (a 1-element fill) under the same launch protocol."""
+    import torch
+    t = torch.zeros(1, device="cuda")
+    _, ev, _ = _time_steps(lambda: t.zero_(), steps, 10, graph_chunk)
+    return ev / steps
+
+
+def _cpu_baseline(p, repeats=5):
+    import oracle
+    best = float("inf")
+    for _ in range(repeats):
+        t0 = time.perf_counter()
+        oracle.bsr_spmm(p.X, p.block_data, p.block_indices, p.index_pointer, p.n)
+        best = min(best, time.perf_counter() - t0)
+    return {"value": p.flops / best / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"the whole '{p.name}' workload, best of {repeats} runs ({best * 1e3:.1f} ms each); "
+                      "plain double-precision loops, a correctness reference and not a tuned CPU SpMM"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--graph-chunk", type=int, default=100,
+                    help="launches per captured HIP graph (0 = plain launches only)")
+    ap.add_argument("--no-all-configs", action="store_true", help="skip the per-configuration table")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the product needs no exchange between GPUs; "
+                 "see DESIGN.md for how it would shard). Use --gpus 1.")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    import paper_2007_13055_amd as lib
+    lib.load_library()
+    torch.cuda.set_device(0)
+    chunk = a.graph_chunk if (a.graph_chunk > 0 and a.steps % a.graph_chunk == 0) else 0
+
+    p, W, r = _bench_config(HEADLINE, a.steps, a.warmup, chunk)
+    sec = r["wall_s"] / a.steps
+    out = {
+        "metric": "effective TFLOP/s of bsr_spmm (2*m*nnzb*bs_r*bs_c per call)",
+        "value": p.flops / sec / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "ffn: X fp32 (128,3072) N(0,1); W (3072,3072) BSR 32x32, 922 blocks (density 0.10) "
+                               "uniform without replacement, N(0,0.02); Y fp32",
+                   "m": p.m, "k": p.k, "n": p.n, "bs_r": p.bs_r, "bs_c": p.bs_c, "nnzb": p.nnzb,
+                   "path": r["path"], "launch": r["mode"], "seed": p.seed},
+        "roofline": _roofline(p, r["event_s"] / a.steps),
+        "eager_ms_per_step": r["eager_wall_s"] / a.steps * 1e3,
+        "launch_floor_us": _launch_floor(a.steps, chunk) * 1e6,
+    }
+    out["cpu_baseline"] = None if a.no_cpu else _cpu_baseline(p)
+
+    if not a.no_all_configs:
+        table = {}
+        for cid in (1, 3, 4, 5):
+            steps = 200 if cid == 5 else a.steps
+            ch = chunk if steps % max(chunk, 1) == 0 else 0
+            q, Wq, rq = _bench_config(cid, steps, 20, ch)
+            s = rq["event_s"] / steps
+            t_hbm = q.algorithmic_bytes() / (PEAK_HBM_GBS * 1e9)
+            t_mfma = q.flops / (PEAK_MFMA_TFLOPS[q.in_dtype] * 1e12)
+            table[q.name] = {"us_per_call": s * 1e6, "tflops": q.flops / s / 1e12, "hbm_frac": t_hbm / s,
+                             "mfma_frac": t_mfma / s, "bound": "mfma" if t_mfma >= t_hbm else "hbm",
+                             "path": rq["path"], "launch": rq["mode"],
+                             "eager_us_per_call": rq["eager_wall_s"] / steps * 1e6}
+            del Wq
+        out["per_config"] = table
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
