@@ -1,7 +1,9 @@
 // Host side of libbsr_spmm: structural validation, the block-row plan, handle life cycle and
 // kernel-family dispatch.  Nothing here allocates device memory.
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
+#include <string>
 #include <new>
 #include <numeric>
 
@@ -23,14 +25,41 @@ bsr_status check_shape(int64_t n, int64_t k, int32_t bs_r, int32_t bs_c, int64_t
 
 size_t plan_bytes(int64_t R, int64_t nnzb)
 {
-    // row order (R int32) plus room for per-row work lists; rounded up to 256 bytes
-    size_t b = 16 * (size_t)(R + nnzb) + 256;
+    // row order (R int32, padded to 256 B) + row descriptors (16 int32 per block-row) + spare room
+    // for per-block work lists; rounded up to 256 bytes
+    size_t b = 128 * (size_t)R + 16 * (size_t)nnzb + 1024;
     return (b + 255) & ~(size_t)255;
 }
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 }  // namespace
+
+tune_opts read_tune_env()
+{
+    tune_opts t;
+    const char* e = std::getenv("BSR_SPMM_TUNE");
+    if (!e) return t;
+    std::string s(e);
+    size_t pos = 0;
+    while (pos < s.size()) {
+        size_t end = s.find(',', pos);
+        if (end == std::string::npos) end = s.size();
+        const std::string kv = s.substr(pos, end - pos);
+        const size_t eq = kv.find('=');
+        if (eq != std::string::npos) {
+            const std::string key = kv.substr(0, eq);
+            const int val = std::atoi(kv.c_str() + eq + 1);
+            if (key == "variant") t.variant = val;
+            else if (key == "nw") t.nw = val;
+            else if (key == "mt") t.mt = val;
+            else if (key == "a") t.a = val;
+            else if (key == "b") t.b = val;
+        }
+        pos = end + 1;
+    }
+    return t;
+}
 
 extern "C" {
 
@@ -92,16 +121,30 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
     //      their natural order and neighbouring rows stay neighbours in the launch) ----
     std::vector<int32_t> cnt((size_t)R);
     for (int64_t r = 0; r < R; ++r) cnt[(size_t)r] = index_pointer_host[r + 1] - index_pointer_host[r];
-    W->staging.resize((size_t)std::max<int64_t>(R, 1));
+    const size_t order_words = (((size_t)R * 4 + 255) & ~(size_t)255) / 4;   // row_order, padded to 256 B
+    W->staging.assign(order_words + (size_t)R * kRowDescWords + 1, 0);
     std::iota(W->staging.begin(), W->staging.begin() + R, 0);
     std::stable_sort(W->staging.begin(), W->staging.begin() + R,
                      [&](int32_t a, int32_t b) { return cnt[(size_t)a] > cnt[(size_t)b]; });
+    // Row descriptors, in slot order: everything a workgroup needs to start on its block-row in
+    // ONE read (block-row, first stored block, block count, the first block-columns), instead of
+    // the dependent chain row_order -> index_pointer -> block_indices.
+    for (int64_t s = 0; s < R; ++s) {
+        const int32_t r = W->staging[(size_t)s];
+        int32_t* d = W->staging.data() + order_words + (size_t)s * kRowDescWords;
+        d[0] = r;
+        d[1] = index_pointer_host[r];
+        d[2] = cnt[(size_t)r];
+        for (int j = 0; j < kRowDescCols && j < cnt[(size_t)r]; ++j) d[3 + j] = block_indices_host[d[1] + j];
+    }
     W->max_row_blocks = R ? *std::max_element(cnt.begin(), cnt.end()) : 0;
     W->empty_rows = (int32_t)std::count(cnt.begin(), cnt.end(), 0);
     W->mean_row_blocks = R ? (double)nnzb / (double)R : 0.0;
     W->row_order = static_cast<const int32_t*>(workspace_dev);
+    W->row_desc = W->row_order + order_words;
     if (R > 0) {
-        hipError_t e = hipMemcpyAsync(workspace_dev, W->staging.data(), sizeof(int32_t) * (size_t)R,
+        hipError_t e = hipMemcpyAsync(workspace_dev, W->staging.data(),
+                                      sizeof(int32_t) * (order_words + (size_t)R * kRowDescWords),
                                       hipMemcpyHostToDevice, (hipStream_t)hip_stream);
         if (e != hipSuccess) { delete W; return BSR_ERR_HIP; }
     }

@@ -9,6 +9,9 @@
 
 #include "bsr_spmm.h"
 
+constexpr int kRowDescWords = 16;                 // int32 per row descriptor (64 bytes)
+constexpr int kRowDescCols = kRowDescWords - 3;   // block-columns held inline
+
 // Host-side description of one W.  Device pointers are borrowed from the caller.
 struct bsr_matrix {
     int64_t n = 0, k = 0, nnzb = 0;
@@ -23,6 +26,9 @@ struct bsr_matrix {
     // Block-rows ordered by stored-block count, longest first; a workgroup's slot s works on
     // block-row row_order[s], so the long rows are dispatched before the short ones.
     const int32_t* row_order = nullptr;      // device, [R]
+    // Per slot, kRowDescWords int32: {block-row, first stored block, block count, the first
+    // kRowDescCols block-columns}: one read starts a workgroup (device, [R][kRowDescWords]).
+    const int32_t* row_desc = nullptr;
     int32_t max_row_blocks = 0;              // longest block-row
     int32_t empty_rows = 0;                  // block-rows with no stored block
     double mean_row_blocks = 0.0;
@@ -39,7 +45,46 @@ struct spmm_args {
     hipStream_t stream;
 };
 
+// Development knobs, read from the environment variable BSR_SPMM_TUNE ("key=value,key=value").
+// Unset keys are 0 and mean "the library's own choice".
+//   variant  1 direct, 2 ksplit  (matrix-core kernel variant)
+//   nw       wavefronts per workgroup      mt   MFMA tiles along m per wavefront
+struct tune_opts {
+    int variant = 0, nw = 0, mt = 0, a = 0, b = 0;
+};
+tune_opts read_tune_env();
+
 // Each returns BSR_OK, BSR_ERR_UNSUPPORTED (shape not covered by that family) or BSR_ERR_HIP.
 bsr_status launch_wave(const spmm_args& a);
 bsr_status launch_mfma(const spmm_args& a);
 bool mfma_supports(const bsr_matrix* W);
+
+// matrix-core kernel variants (bsr_mfma*.hip)
+bsr_status launch_mfma_direct(const spmm_args& a, const tune_opts& t);
+bsr_status launch_mfma_ksplit(const spmm_args& a, const tune_opts& t);
+
+// Expands to a chain of `if (shape matches) return FN<T, O, BR, BC>(args...)` over the block
+// shapes the matrix-core kernels are instantiated for.
+#define BSR_MFMA_SHAPES(FN, T, O, br, bc, ...)                                             \
+    do {                                                                                   \
+        if (br == 16 && bc == 16) return FN<T, O, 16, 16>(__VA_ARGS__);                    \
+        if (br == 16 && bc == 32) return FN<T, O, 16, 32>(__VA_ARGS__);                    \
+        if (br == 16 && bc == 64) return FN<T, O, 16, 64>(__VA_ARGS__);                    \
+        if (br == 32 && bc == 16) return FN<T, O, 32, 16>(__VA_ARGS__);                    \
+        if (br == 32 && bc == 32) return FN<T, O, 32, 32>(__VA_ARGS__);                    \
+        if (br == 32 && bc == 64) return FN<T, O, 32, 64>(__VA_ARGS__);                    \
+        if (br == 64 && bc == 16) return FN<T, O, 64, 16>(__VA_ARGS__);                    \
+        if (br == 64 && bc == 32) return FN<T, O, 64, 32>(__VA_ARGS__);                    \
+        if (br == 64 && bc == 64) return FN<T, O, 64, 64>(__VA_ARGS__);                    \
+    } while (0)
+
+// Dispatch on (input type, output type) to FN<T, O, BR, BC>(args...).
+#define BSR_MFMA_DISPATCH(FN, W, y_dtype, ...)                                                            \
+    do {                                                                                                  \
+        const int br_ = (W)->bs_r, bc_ = (W)->bs_c;                                                       \
+        if ((W)->dtype == BSR_F32) BSR_MFMA_SHAPES(FN, float, float, br_, bc_, __VA_ARGS__);              \
+        if ((W)->dtype == BSR_F16 && (y_dtype) == BSR_F32) BSR_MFMA_SHAPES(FN, _Float16, float, br_, bc_, __VA_ARGS__);   \
+        if ((W)->dtype == BSR_F16) BSR_MFMA_SHAPES(FN, _Float16, _Float16, br_, bc_, __VA_ARGS__);        \
+        if ((W)->dtype == BSR_BF16 && (y_dtype) == BSR_F32) BSR_MFMA_SHAPES(FN, __bf16, float, br_, bc_, __VA_ARGS__);    \
+        if ((W)->dtype == BSR_BF16) BSR_MFMA_SHAPES(FN, __bf16, __bf16, br_, bc_, __VA_ARGS__);           \
+    } while (0)

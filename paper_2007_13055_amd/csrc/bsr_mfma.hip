@@ -14,118 +14,11 @@
 // one, so a lane's operand is a contiguous run of CH elements of a block row / an X row.  The
 // lane groups split the bs_c columns of a block into 64/MM contiguous runs; W and X use the same
 // split, so the sum over c is complete whatever order the instruction takes its k in.
-#include <type_traits>
+#include "bsr_mfma_common.h"
 
-#include "bsr_internal.h"
+using namespace bsr_dev;
 
 namespace {
-
-typedef _Float16 f16_t;
-typedef __bf16 bf16_t;
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef short i16x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-template <typename O> __device__ __forceinline__ O from_f32(float v);
-template <> __device__ __forceinline__ f16_t from_f32<f16_t>(float v) { return (f16_t)v; }     // nearest-even
-template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }   // nearest-even
-
-// A lane's operand: CH contiguous elements of type T, kept as 32-bit words.
-template <typename T, int CH>
-struct Frag {
-    static constexpr int BYTES = CH * (int)sizeof(T);
-    static constexpr int WORDS = BYTES / 4;
-    static_assert(BYTES % 8 == 0, "a lane's run must be a multiple of 8 bytes");
-    uint32_t w[WORDS];
-
-    __device__ __forceinline__ void load(const T* __restrict__ p)
-    {
-        if constexpr (BYTES % 16 == 0) {
-            const u32x4* q = reinterpret_cast<const u32x4*>(p);
-#pragma unroll
-            for (int i = 0; i < BYTES / 16; ++i) {
-                const u32x4 v = q[i];
-                w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
-            }
-        } else {
-            const u32x2* q = reinterpret_cast<const u32x2*>(p);
-#pragma unroll
-            for (int i = 0; i < BYTES / 8; ++i) {
-                const u32x2 v = q[i];
-                w[2 * i] = v.x; w[2 * i + 1] = v.y;
-            }
-        }
-    }
-};
-
-template <int MM> struct AccT { typedef f32x16 type; };
-template <> struct AccT<16> { typedef f32x4 type; };
-
-// acc += Wfrag (rows) x Xfrag (columns), all of the lane's CH elements.
-template <typename T, int MM, int CH>
-__device__ __forceinline__ void mfma_frag(typename AccT<MM>::type& acc, const Frag<T, CH>& a, const Frag<T, CH>& b)
-{
-    if constexpr (std::is_same<T, float>::value) {
-#pragma unroll
-        for (int s = 0; s < CH; ++s) {
-            const float av = __builtin_bit_cast(float, a.w[s]);
-            const float bv = __builtin_bit_cast(float, b.w[s]);
-            if constexpr (MM == 32) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc, 0, 0, 0);
-            else                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc, 0, 0, 0);
-        }
-    } else if constexpr (CH % 8 == 0) {
-#pragma unroll
-        for (int s = 0; s < CH / 8; ++s) {
-            const u32x4 ar = {a.w[4 * s], a.w[4 * s + 1], a.w[4 * s + 2], a.w[4 * s + 3]};
-            const u32x4 br = {b.w[4 * s], b.w[4 * s + 1], b.w[4 * s + 2], b.w[4 * s + 3]};
-            if constexpr (std::is_same<T, f16_t>::value) {
-                const f16x8 av = __builtin_bit_cast(f16x8, ar), bv = __builtin_bit_cast(f16x8, br);
-                if constexpr (MM == 32) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv, acc, 0, 0, 0);
-                else                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc, 0, 0, 0);
-            } else {
-                const bf16x8 av = __builtin_bit_cast(bf16x8, ar), bv = __builtin_bit_cast(bf16x8, br);
-                if constexpr (MM == 32) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
-                else                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bv, acc, 0, 0, 0);
-            }
-        }
-    } else {
-        static_assert(std::is_same<T, float>::value || CH % 4 == 0, "16-bit runs come in multiples of 4");
-#pragma unroll
-        for (int s = 0; s < CH / 4; ++s) {
-            const u32x2 ar = {a.w[2 * s], a.w[2 * s + 1]};
-            const u32x2 br = {b.w[2 * s], b.w[2 * s + 1]};
-            if constexpr (std::is_same<T, f16_t>::value) {
-                const f16x4 av = __builtin_bit_cast(f16x4, ar), bv = __builtin_bit_cast(f16x4, br);
-                if constexpr (MM == 32) acc = __builtin_amdgcn_mfma_f32_32x32x8f16(av, bv, acc, 0, 0, 0);
-                else                    acc = __builtin_amdgcn_mfma_f32_16x16x16f16(av, bv, acc, 0, 0, 0);
-            } else {
-                const i16x4 av = __builtin_bit_cast(i16x4, ar), bv = __builtin_bit_cast(i16x4, br);
-                if constexpr (MM == 32) acc = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(av, bv, acc, 0, 0, 0);
-                else                    acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, bv, acc, 0, 0, 0);
-            }
-        }
-    }
-}
-
-// Store 4 consecutive columns of one row of Y (the 4 accumulator values a lane holds for 4
-// consecutive rows of the MFMA result).
-template <typename O>
-__device__ __forceinline__ void store4(O* __restrict__ dst, float v0, float v1, float v2, float v3)
-{
-    if constexpr (std::is_same<O, float>::value) {
-        const f32x4 v = {v0, v1, v2, v3};
-        *reinterpret_cast<f32x4*>(dst) = v;
-    } else {
-        typedef O o4 __attribute__((ext_vector_type(4)));
-        const o4 v = {from_f32<O>(v0), from_f32<O>(v1), from_f32<O>(v2), from_f32<O>(v3)};
-        *reinterpret_cast<o4*>(dst) = v;
-    }
-}
 
 // Direct kernel: operands go from global memory (L1/L2) straight into registers.
 //   MM   MFMA tile edge: 32 when bs_r >= 32, else 16          NA = BS_R / MM   result tiles along n
@@ -221,7 +114,7 @@ __global__ __launch_bounds__(256) void bsr_mfma_direct(const T* __restrict__ X, 
 }
 
 template <typename T, typename O, int BS_R, int BS_C>
-bsr_status launch_shape(const spmm_args& a)
+bsr_status launch_direct_shape(const spmm_args& a, const tune_opts& tune)
 {
     const bsr_matrix* W = a.W;
     const int m = (int)a.m, n = (int)W->n, k = (int)W->k, R = W->R;
@@ -240,24 +133,20 @@ bsr_status launch_shape(const spmm_args& a)
     // Tile height: enough workgroups to fill 256 CUs several times over when m allows it, taller
     // wavefront tiles (more reuse of each W block) when m is large.
     const int sub = (m + MM - 1) / MM;                 // MFMA tiles along m
-    if (sub >= 64) return go(std::integral_constant<int, 2>{}, 4);
-    if (sub >= 8) return go(std::integral_constant<int, 1>{}, 4);
-    return go(std::integral_constant<int, 1>{}, 1);
-}
-
-template <typename T, typename O>
-bsr_status launch_dtype(const spmm_args& a)
-{
-    const int br = a.W->bs_r, bc = a.W->bs_c;
-#define BSR_CASE(BR, BC) if (br == BR && bc == BC) return launch_shape<T, O, BR, BC>(a)
-    BSR_CASE(16, 16); BSR_CASE(16, 32); BSR_CASE(16, 64);
-    BSR_CASE(32, 16); BSR_CASE(32, 32); BSR_CASE(32, 64);
-    BSR_CASE(64, 16); BSR_CASE(64, 32); BSR_CASE(64, 64);
-#undef BSR_CASE
-    return BSR_ERR_UNSUPPORTED;
+    int mt = sub >= 64 ? 2 : 1, waves = sub >= 8 ? 4 : 1;
+    if (tune.mt == 1 || tune.mt == 2) mt = tune.mt;
+    if (tune.nw >= 1 && tune.nw <= 4) waves = tune.nw;
+    if (mt == 2) return go(std::integral_constant<int, 2>{}, waves);
+    return go(std::integral_constant<int, 1>{}, waves);
 }
 
 }  // namespace
+
+bsr_status launch_mfma_direct(const spmm_args& a, const tune_opts& t)
+{
+    BSR_MFMA_DISPATCH(launch_direct_shape, a.W, a.y_dtype, a, t);
+    return BSR_ERR_UNSUPPORTED;
+}
 
 bool mfma_supports(const bsr_matrix* W)
 {
@@ -267,11 +156,19 @@ bool mfma_supports(const bsr_matrix* W)
     return r_ok && c_ok && W->R > 0;
 }
 
+// Which matrix-core kernel serves this product.
+//   ksplit  few tiles along m (m/MM small): the stored blocks of a block-row are spread over the
+//           wavefronts of a workgroup, otherwise most of the chip would idle
+//   direct  everything else
 bsr_status launch_mfma(const spmm_args& a)
 {
-    const bsr_dtype in = a.W->dtype, out = a.y_dtype;
-    if (in == BSR_F32) return launch_dtype<float, float>(a);
-    if (in == BSR_F16) return out == BSR_F32 ? launch_dtype<f16_t, float>(a) : launch_dtype<f16_t, f16_t>(a);
-    if (in == BSR_BF16) return out == BSR_F32 ? launch_dtype<bf16_t, float>(a) : launch_dtype<bf16_t, bf16_t>(a);
-    return BSR_ERR_DTYPE;
+    const tune_opts t = read_tune_env();
+    int variant = t.variant;
+    if (variant == 0) {
+        const int MM = a.W->bs_r >= 32 ? 32 : 16;
+        const int64_t sub = (a.m + MM - 1) / MM;
+        variant = (sub * a.W->R < 4096 && a.W->mean_row_blocks > 1.5) ? 2 : 1;
+    }
+    if (variant == 2) return launch_mfma_ksplit(a, t);
+    return launch_mfma_direct(a, t);
 }
