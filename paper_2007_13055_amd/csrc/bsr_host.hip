@@ -140,6 +140,14 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
     W->max_row_blocks = R ? *std::max_element(cnt.begin(), cnt.end()) : 0;
     W->empty_rows = (int32_t)std::count(cnt.begin(), cnt.end(), 0);
     W->mean_row_blocks = R ? (double)nnzb / (double)R : 0.0;
+    // bins (paper, Discussion: a few rows with many blocks beside many sparse rows): empty rows,
+    // ordinary rows, and "long" rows -- more than 4x the mean and more than 8 blocks -- which the
+    // tiled kernel starts ahead of everything else.  Slots are sorted, so the long rows lead.
+    W->long_rows = 0;
+    for (int64_t s = 0; s < R && s < R - 1; ++s) {
+        const int32_t c = cnt[(size_t)W->staging[(size_t)s]];
+        if (c > 8 && (double)c > 4.0 * W->mean_row_blocks) ++W->long_rows; else break;
+    }
     W->row_order = static_cast<const int32_t*>(workspace_dev);
     W->row_desc = W->row_order + order_words;
     if (R > 0) {

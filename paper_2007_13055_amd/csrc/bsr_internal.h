@@ -30,6 +30,7 @@ struct bsr_matrix {
     // kRowDescCols block-columns}: one read starts a workgroup (device, [R][kRowDescWords]).
     const int32_t* row_desc = nullptr;
     int32_t max_row_blocks = 0;              // longest block-row
+    int32_t long_rows = 0;                   // leading slots whose block count is > 4x the mean and > 8 ("long" bin)
     int32_t empty_rows = 0;                  // block-rows with no stored block
     double mean_row_blocks = 0.0;
     std::vector<int32_t> staging;            // host copy of what was uploaded (kept for the async copy)
@@ -47,7 +48,7 @@ struct spmm_args {
 
 // Development knobs, read from the environment variable BSR_SPMM_TUNE ("key=value,key=value").
 // Unset keys are 0 and mean "the library's own choice".
-//   variant  1 direct, 2 ksplit  (matrix-core kernel variant)
+//   variant  1 direct, 2 ksplit, 3 tile  (matrix-core kernel variant)
 //   nw       wavefronts per workgroup      mt   MFMA tiles along m per wavefront
 struct tune_opts {
     int variant = 0, nw = 0, mt = 0, a = 0, b = 0;
@@ -62,6 +63,7 @@ bool mfma_supports(const bsr_matrix* W);
 // matrix-core kernel variants (bsr_mfma*.hip)
 bsr_status launch_mfma_direct(const spmm_args& a, const tune_opts& t);
 bsr_status launch_mfma_ksplit(const spmm_args& a, const tune_opts& t);
+bsr_status launch_mfma_tile(const spmm_args& a, const tune_opts& t);
 
 // Expands to a chain of `if (shape matches) return FN<T, O, BR, BC>(args...)` over the block
 // shapes the matrix-core kernels are instantiated for.

@@ -159,16 +159,22 @@ bool mfma_supports(const bsr_matrix* W)
 // Which matrix-core kernel serves this product.
 //   ksplit  few tiles along m (m/MM small): the stored blocks of a block-row are spread over the
 //           wavefronts of a workgroup, otherwise most of the chip would idle
-//   direct  everything else
+//   tile    many rows of X and blocks at least 32 rows tall: 128 x bs_r tiles of Y, the W block and
+//           the X tile staged in LDS with coalesced reads, XCD-aware launch order
+//   direct  everything else (operands straight from global memory)
 bsr_status launch_mfma(const spmm_args& a)
 {
-    const tune_opts t = read_tune_env();
+    tune_opts t = read_tune_env();
     int variant = t.variant;
     if (variant == 0) {
         const int MM = a.W->bs_r >= 32 ? 32 : 16;
         const int64_t sub = (a.m + MM - 1) / MM;
-        variant = (sub * a.W->R < 4096 && a.W->mean_row_blocks > 1.5) ? 2 : 1;
+        if (sub * a.W->R < 4096 && a.W->mean_row_blocks > 1.5) variant = 2;
+        else if (a.W->bs_r >= 32 && a.m >= 512) variant = 3;
+        else variant = 1;
+        if (variant == 3 && t.mt == 0) t.mt = 1;
     }
     if (variant == 2) return launch_mfma_ksplit(a, t);
+    if (variant == 3) return launch_mfma_tile(a, t);
     return launch_mfma_direct(a, t);
 }

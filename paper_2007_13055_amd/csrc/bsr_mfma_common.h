@@ -116,4 +116,19 @@ __device__ __forceinline__ void store4(O* __restrict__ dst, float v0, float v1, 
     }
 }
 
+// As store4, with the non-temporal hint: the line is not kept in L2 for re-use (Y is written once
+// and never read by the kernel, so it should not push re-used X tiles out of the cache).
+template <typename O>
+__device__ __forceinline__ void store4_nt(O* __restrict__ dst, float v0, float v1, float v2, float v3)
+{
+    if constexpr (std::is_same<O, float>::value) {
+        const f32x4 v = {v0, v1, v2, v3};
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst));
+    } else {
+        typedef O o4 __attribute__((ext_vector_type(4)));
+        const o4 v = {from_f32<O>(v0), from_f32<O>(v1), from_f32<O>(v2), from_f32<O>(v3)};
+        __builtin_nontemporal_store(v, reinterpret_cast<o4*>(dst));
+    }
+}
+
 }  // namespace bsr_dev

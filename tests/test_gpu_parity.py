@@ -230,3 +230,33 @@ def test_repeat_calls_are_bitwise_identical(oracle_mod):
     Y1, W = gpu_product(p)
     Y2, _ = gpu_product(p, W=W)
     assert np.array_equal(Y1, Y2)
+
+
+# ------------------------------------------------------------------ every matrix-core kernel variant
+# BSR_SPMM_TUNE is the library's development knob; "variant" pins the matrix-core kernel:
+# 1 direct (operands from global memory), 2 k-split (few rows of X), 3 LDS-staged tiles (many rows).
+@pytest.mark.parametrize("variant,extra", [(1, ""), (1, ",mt=2,nw=4"), (2, ""), (2, ",nw=3,a=1"), (3, ",mt=1,a=1"),
+                                           (3, ",mt=1,a=3"), (3, ",mt=2,a=2"), (3, ",mt=1,a=2,b=3")])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_mfma_kernel_variants(oracle_mod, monkeypatch, variant, extra, dtype):
+    monkeypatch.setenv("BSR_SPMM_TUNE", f"variant={variant}{extra}")
+    shapes = [(32, 32), (64, 64), (32, 64), (64, 16)] if variant == 3 else [(16, 16), (32, 32), (64, 64), (16, 64)]
+    for (bs_r, bs_c) in shapes:
+        for m in (5, 130, 700):                       # partial tile, two tiles, several tiles + ragged tail
+            counts = np.array([0, 1, 2, 3, 40, 5, 0, 17, 9])      # empty rows, short rows, one long row
+            counts = np.minimum(counts, 40)
+            p = wl.make_problem("v", m, 40 * bs_c, counts.shape[0] * bs_r, bs_r, bs_c, dtype, dtype,
+                                ("counts", counts), ("normal", 1.0), ("normal", 1.0), 300 + m + bs_r + bs_c)
+            Yo, So = oracle_of(oracle_mod, p)
+            Yg, W = gpu_product(p, path=MFMA)
+            check(Yg, Yo, So, p.tau, f"variant {variant}{extra} {dtype} {bs_r}x{bs_c} m={m}", out_dtype=dtype)
+            Yg2, _ = gpu_product(p, path=MFMA, W=W)
+            assert np.array_equal(Yg, Yg2), "two runs differ: race"
+
+
+def test_tile_kernel_small_integers_bitwise(oracle_mod, monkeypatch):
+    monkeypatch.setenv("BSR_SPMM_TUNE", "variant=3,mt=1,a=2")
+    p = wl.small_integer_problem(600, 16 * 64, 6 * 64, 64, 64, 0.5, seed=21, in_dtype="f16", out_dtype="f32", lo=-2, hi=2)
+    Yo, So = oracle_of(oracle_mod, p)
+    Yg, _ = gpu_product(p, path=MFMA)
+    assert np.array_equal(Yg, Yo)
