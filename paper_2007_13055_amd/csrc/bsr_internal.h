@@ -64,6 +64,8 @@ bool mfma_supports(const bsr_matrix* W);
 bsr_status launch_mfma_direct(const spmm_args& a, const tune_opts& t);
 bsr_status launch_mfma_ksplit(const spmm_args& a, const tune_opts& t);
 bsr_status launch_mfma_tile(const spmm_args& a, const tune_opts& t);
+bsr_status launch_mfma_stripe(const spmm_args& a, const tune_opts& t);
+bool mfma_stripe_supports(const bsr_matrix* W, int tm);   // 16x16 blocks, 16-bit type, tm rows of X fit in LDS
 
 // Expands to a chain of `if (shape matches) return FN<T, O, BR, BC>(args...)` over the block
 // shapes the matrix-core kernels are instantiated for.

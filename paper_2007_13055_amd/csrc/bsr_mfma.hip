@@ -161,6 +161,8 @@ bool mfma_supports(const bsr_matrix* W)
 //           wavefronts of a workgroup, otherwise most of the chip would idle
 //   tile    many rows of X and blocks at least 32 rows tall: 128 x bs_r tiles of Y, the W block and
 //           the X tile staged in LDS with coalesced reads, XCD-aware launch order
+//   stripe  16x16 blocks of a 16-bit type, many rows of X, and 64 full rows of X fit in LDS: the
+//           stripe is copied to LDS once and many block-rows are multiplied against it
 //   direct  everything else (operands straight from global memory)
 bsr_status launch_mfma(const spmm_args& a)
 {
@@ -171,10 +173,12 @@ bsr_status launch_mfma(const spmm_args& a)
         const int64_t sub = (a.m + MM - 1) / MM;
         if (sub * a.W->R < 4096 && a.W->mean_row_blocks > 1.5) variant = 2;
         else if (a.W->bs_r >= 32 && a.m >= 512) variant = 3;
+        else if (a.m >= 256 && mfma_stripe_supports(a.W, 64)) variant = 4;
         else variant = 1;
         if (variant == 3 && t.mt == 0) t.mt = 1;
     }
     if (variant == 2) return launch_mfma_ksplit(a, t);
     if (variant == 3) return launch_mfma_tile(a, t);
+    if (variant == 4) return launch_mfma_stripe(a, t);
     return launch_mfma_direct(a, t);
 }

@@ -260,3 +260,23 @@ def test_tile_kernel_small_integers_bitwise(oracle_mod, monkeypatch):
     Yo, So = oracle_of(oracle_mod, p)
     Yg, _ = gpu_product(p, path=MFMA)
     assert np.array_equal(Yg, Yo)
+
+
+@pytest.mark.parametrize("extra", ["", ",mt=1", ",mt=2,a=3", ",mt=4,a=1", ",mt=4,a=7"])
+@pytest.mark.parametrize("dtype,out", [("bf16", "bf16"), ("f16", "f16"), ("bf16", "f32")])
+def test_stripe_kernel_variant(oracle_mod, monkeypatch, extra, dtype, out):
+    """variant 4: 16x16 blocks of a 16-bit type, the X stripe staged in LDS (the 'batched' regime)."""
+    monkeypatch.setenv("BSR_SPMM_TUNE", "variant=4" + extra)
+    for m, R, C in ((5, 3, 4), (70, 9, 12), (300, 50, 48), (129, 13, 7)):
+        rng = np.random.default_rng(m + R)
+        counts = rng.integers(0, min(C, 21) + 1, size=R)
+        counts[0] = 0
+        counts[R // 2] = min(C, 19)                    # an odd count, longer than one chunk of 8 pairs
+        counts[-1] = 1
+        p = wl.make_problem("st", m, C * 16, R * 16, 16, 16, dtype, out, ("counts", counts), ("normal", 1.0),
+                            ("normal", 1.0), 400 + m)
+        Yo, So = oracle_of(oracle_mod, p)
+        Yg, W = gpu_product(p, path=MFMA)
+        check(Yg, Yo, So, p.tau, f"stripe{extra} {dtype}->{out} m={m} R={R} C={C}", out_dtype=out)
+        Yg2, _ = gpu_product(p, path=MFMA, W=W)
+        assert np.array_equal(Yg, Yg2), "two runs differ: race"
