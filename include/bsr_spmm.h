@@ -45,7 +45,8 @@ typedef enum {
     BSR_ERR_INDEX = 4,       /* a block_indices entry outside [0, k/bs_c) */
     BSR_ERR_DTYPE = 5,       /* unknown dtype, or y_dtype neither the input type nor BSR_F32 */
     BSR_ERR_ALIGN = 6,       /* a device pointer is not 16-byte aligned */
-    BSR_ERR_WORKSPACE = 7,   /* workspace smaller than bsr_workspace_size() reports */
+    BSR_ERR_WORKSPACE = 7,   /* workspace smaller than bsr_workspace_size() reports, or the chosen kernel needs
+                                scratch (bsr_scratch_size) that has not been lent with bsr_set_scratch */
     BSR_ERR_HIP = 8,         /* a HIP runtime call failed (launch, copy) */
     BSR_ERR_UNSUPPORTED = 9  /* the requested kernel path cannot handle this block shape */
 } bsr_status;
@@ -115,11 +116,29 @@ void bsr_destroy(bsr_matrix* W);
  *   y_dtype W's dtype or BSR_F32; the fp32 accumulator is rounded to nearest-even on store
  *   m       any value >= 0 (m == 0 returns BSR_OK without device work)
  * Every element of Y is written; columns of an empty block-row are exact zeros.  Asynchronous on
- * `hip_stream`; no hidden synchronisation; safe to call concurrently on one handle.
+ * `hip_stream`; no hidden synchronisation; safe to call concurrently on one handle unless the
+ * product uses lent scratch (see bsr_set_scratch).
  * Errors: NULL, SHAPE (m < 0 or m*max(k,n) >= 2^31), DTYPE, ALIGN, HIP.
  */
 bsr_status bsr_spmm(const bsr_matrix* W, int64_t m, const void* X_dev, void* Y_dev,
                     bsr_dtype y_dtype, void* hip_stream);
+
+/*
+ * Scratch.  Some kernels need device memory beyond X, W and Y for the duration of one product:
+ * the thin-block matrix-core path (bs_r = 16, bs_c = 1, fp32) first writes a transposed copy of
+ * X, m*k floats, so that the columns of X that the stored blocks select (Background: the block's
+ * column index picks the part of X) become contiguous rows.  The library does not allocate it.
+ *   bsr_scratch_size  bytes such a product with m rows would use (0 when no kernel for this W
+ *                     needs scratch); multiple of 256.
+ *   bsr_set_scratch   lends `bytes` of DEVICE memory (16-byte aligned) to the handle, or takes it
+ *                     back with NULL.  The memory stays owned by the caller and must outlive its
+ *                     use; products that use it must not overlap in time on one handle (they
+ *                     share it), i.e. keep them on one stream.
+ * Without (enough) scratch BSR_PATH_AUTO uses the wavefront-reduction kernels for such W and
+ * BSR_PATH_MFMA returns BSR_ERR_WORKSPACE.
+ */
+bsr_status bsr_scratch_size(const bsr_matrix* W, int64_t m, size_t* bytes);
+bsr_status bsr_set_scratch(bsr_matrix* W, void* scratch_dev, size_t bytes);
 
 /*
  * As bsr_spmm() with the kernel family fixed.  BSR_PATH_MFMA needs bs_r in {16, 32, 64},

@@ -47,9 +47,12 @@ def load_library():
     lib.bsr_spmm.argtypes = [vp, i64, vp, vp, ctypes.c_int, vp]
     lib.bsr_spmm_ex.argtypes = [vp, i64, vp, vp, ctypes.c_int, ctypes.c_int, vp]
     lib.bsr_query_path.argtypes = [vp, i64, ctypes.POINTER(ctypes.c_int)]
+    lib.bsr_scratch_size.argtypes = [vp, i64, ctypes.POINTER(sz)]
+    lib.bsr_set_scratch.argtypes = [vp, vp, sz]
     lib.bsr_status_string.argtypes = [ctypes.c_int]
     lib.bsr_status_string.restype = ctypes.c_char_p
-    for f in ("bsr_validate", "bsr_workspace_size", "bsr_create", "bsr_spmm", "bsr_spmm_ex", "bsr_query_path"):
+    for f in ("bsr_validate", "bsr_workspace_size", "bsr_create", "bsr_spmm", "bsr_spmm_ex", "bsr_query_path",
+              "bsr_scratch_size", "bsr_set_scratch"):
         getattr(lib, f).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -94,10 +97,22 @@ class BsrMatrix:
     def __init__(self, handle, n, k, bs_r, bs_c, dtype, tensors):
         self.handle, self.n, self.k, self.bs_r, self.bs_c, self.dtype = handle, n, k, bs_r, bs_c, dtype
         self._tensors = tensors            # block_data, block_indices, index_pointer, workspace (device)
+        self._scratch = None               # device scratch lent to the handle (see ensure_scratch)
 
     @property
     def block_data(self):
         return self._tensors[0]
+
+    def ensure_scratch(self, m: int):
+        """Lend the handle enough scratch for a product with m rows (torch allocates it; grows only)."""
+        import torch
+        need = bsr_scratch_size(self, m)
+        have = self._scratch.numel() if self._scratch is not None else 0
+        if need > have:
+            self._scratch = torch.empty(need, dtype=torch.uint8, device=self._tensors[0].device)
+            st = load_library().bsr_set_scratch(self.handle, self._scratch.data_ptr(), self._scratch.numel())
+            if st != 0:
+                raise BsrError(st, "bsr_set_scratch")
 
     def close(self):
         if self.handle:
@@ -160,6 +175,7 @@ def bsr_spmm_ex(W: BsrMatrix, X, Y=None, y_dtype=None, path=PATH_AUTO):
         raise ValueError("X must be contiguous and of W's dtype")
     y_dtype = y_dtype or W.dtype
     m = int(X.shape[0])
+    W.ensure_scratch(m)
     if Y is None:
         Y = torch.empty((m, W.n), dtype=_torch_dtype(y_dtype), device=X.device)
     elif tuple(Y.shape) != (m, W.n) or _dtype_name(Y) != y_dtype or not Y.is_contiguous():
@@ -173,6 +189,14 @@ def bsr_spmm_ex(W: BsrMatrix, X, Y=None, y_dtype=None, path=PATH_AUTO):
 
 def bsr_spmm(W: BsrMatrix, X, Y=None, y_dtype=None):
     return bsr_spmm_ex(W, X, Y, y_dtype, PATH_AUTO)
+
+
+def bsr_scratch_size(W: BsrMatrix, m: int) -> int:
+    out = ctypes.c_size_t(0)
+    st = load_library().bsr_scratch_size(W.handle, m, ctypes.byref(out))
+    if st != 0:
+        raise BsrError(st, "bsr_scratch_size")
+    return int(out.value)
 
 
 def bsr_query_path(W: BsrMatrix, m: int) -> int:

@@ -167,7 +167,30 @@ bsr_status bsr_query_path(const bsr_matrix* W, int64_t m, bsr_path* path_out)
     if (!W || !path_out) return BSR_ERR_NULL;
     // Matrix-core tiles are at least 16 rows of X tall: below that most of a tile is padding and
     // the wavefront-reduction kernels (the paper's own regime, m <= 8) stream W once instead.
-    *path_out = (mfma_supports(W) && m >= 16) ? BSR_PATH_MFMA : BSR_PATH_WAVE;
+    // Thin 16x1 fp32 blocks take the matrix-core path when the caller has lent enough scratch for
+    // the transposed copy of X.
+    if (mfma_supports(W) && m >= 16) *path_out = BSR_PATH_MFMA;
+    else if (mfma_thin_supports(W) && m >= 32 && W->scratch && W->scratch_bytes >= mfma_thin_scratch_bytes(W, m))
+        *path_out = BSR_PATH_MFMA;
+    else *path_out = BSR_PATH_WAVE;
+    return BSR_OK;
+}
+
+bsr_status bsr_scratch_size(const bsr_matrix* W, int64_t m, size_t* bytes)
+{
+    if (!W || !bytes) return BSR_ERR_NULL;
+    *bytes = 0;
+    if (m < 0) return BSR_ERR_SHAPE;
+    *bytes = mfma_thin_scratch_bytes(W, m);
+    return BSR_OK;
+}
+
+bsr_status bsr_set_scratch(bsr_matrix* W, void* scratch_dev, size_t bytes)
+{
+    if (!W) return BSR_ERR_NULL;
+    if (scratch_dev && !aligned16(scratch_dev)) return BSR_ERR_ALIGN;
+    W->scratch = scratch_dev;
+    W->scratch_bytes = scratch_dev ? bytes : 0;
     return BSR_OK;
 }
 
@@ -185,6 +208,7 @@ bsr_status bsr_spmm_ex(const bsr_matrix* W, int64_t m, const void* X_dev, void* 
     if (path == BSR_PATH_AUTO) bsr_query_path(W, m, &path);
     spmm_args a{W, m, X_dev, Y_dev, y_dtype, (hipStream_t)hip_stream};
     if (path == BSR_PATH_MFMA) {
+        if (mfma_thin_supports(W)) return launch_mfma_thin(a, read_tune_env());
         if (!mfma_supports(W)) return BSR_ERR_UNSUPPORTED;
         return launch_mfma(a);
     }

@@ -34,6 +34,10 @@ struct bsr_matrix {
     int32_t empty_rows = 0;                  // block-rows with no stored block
     double mean_row_blocks = 0.0;
     std::vector<int32_t> staging;            // host copy of what was uploaded (kept for the async copy)
+    // Optional per-call scratch lent by the caller (bsr_set_scratch): device memory some kernels
+    // need beyond X, W and Y (the thin-block path keeps a transposed copy of X there).
+    void* scratch = nullptr;
+    size_t scratch_bytes = 0;
 };
 
 // Arguments every kernel launcher takes.
@@ -48,8 +52,10 @@ struct spmm_args {
 
 // Development knobs, read from the environment variable BSR_SPMM_TUNE ("key=value,key=value").
 // Unset keys are 0 and mean "the library's own choice".
-//   variant  1 direct, 2 ksplit, 3 tile  (matrix-core kernel variant)
+//   variant  1 direct, 2 ksplit, 3 tile, 4 stripe  (matrix-core kernel variant)
 //   nw       wavefronts per workgroup      mt   MFMA tiles along m per wavefront
+//   a, b     per-variant: ksplit a = blocks per wavefront; tile a = blocks in flight, b-1 = long rows
+//            started first; stripe a = block-row groups; thin a = groups of 4 blocks in flight
 struct tune_opts {
     int variant = 0, nw = 0, mt = 0, a = 0, b = 0;
 };
@@ -66,6 +72,9 @@ bsr_status launch_mfma_ksplit(const spmm_args& a, const tune_opts& t);
 bsr_status launch_mfma_tile(const spmm_args& a, const tune_opts& t);
 bsr_status launch_mfma_stripe(const spmm_args& a, const tune_opts& t);
 bool mfma_stripe_supports(const bsr_matrix* W, int tm);   // 16x16 blocks, 16-bit type, tm rows of X fit in LDS
+bsr_status launch_mfma_thin(const spmm_args& a, const tune_opts& t);    // bs_r = 16, bs_c = 1, fp32; needs scratch
+bool mfma_thin_supports(const bsr_matrix* W);
+size_t mfma_thin_scratch_bytes(const bsr_matrix* W, int64_t m);   // bytes of the transposed copy of X
 
 // Expands to a chain of `if (shape matches) return FN<T, O, BR, BC>(args...)` over the block
 // shapes the matrix-core kernels are instantiated for.

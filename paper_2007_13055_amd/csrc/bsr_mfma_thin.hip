@@ -1,0 +1,197 @@
+// Matrix-core kernels for thin blocks: bs_r = 16, bs_c = 1, fp32.
+//
+// A 16x1 block couples one column of X with 16 columns of Y, so a block-row is a small dense
+// product over a GATHER of X columns:
+//     Y[:, r*16 : r*16+16] = X[:, block_indices[p0..p1)] * block_data[p0..p1, :, 0]
+// Columns of a row-major X are strided (one element per 4k-byte row), so gathering them directly
+// would move a cache line per element.  The product therefore runs in two launches:
+//   1. transpose X (m x k) into a scratch XT (k x m): a column of X becomes a contiguous row;
+//   2. per block-row and per 64 rows of X: MFMA 16x16x4 over 4 stored blocks at a time, the
+//      A operand gathered from XT rows (16 consecutive floats per lane group), the B operand the
+//      4 blocks themselves (64 consecutive floats = one coalesced read).
+// The lanes that share an output element's reduction are inside the matrix core here; what the
+// paper's reduction kernels do with explicit cross-thread sums (Sections 4.4.2-4.4.3) the MFMA
+// does across its k = 4 lane groups.
+#include "bsr_mfma_common.h"
+
+using namespace bsr_dev;
+
+namespace {
+
+// XT[c][i] = X[i][c]; 64x64 tiles through LDS, 16 bytes per lane on both sides.
+__global__ __launch_bounds__(256) void transpose_f32(const float* __restrict__ X, float* __restrict__ XT, int m, int k)
+{
+    __shared__ float tile[64][65];
+    const int c0 = blockIdx.x * 64, i0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;       // 16 x 16
+    const bool full = c0 + 64 <= k && i0 + 64 <= m && (k & 3) == 0 && (m & 3) == 0;
+    if (full) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int i = ty + 16 * j;
+            const f32x4 v = *reinterpret_cast<const f32x4*>(X + (size_t)(i0 + i) * k + c0 + 4 * tx);
+            tile[i][4 * tx] = v.x; tile[i][4 * tx + 1] = v.y; tile[i][4 * tx + 2] = v.z; tile[i][4 * tx + 3] = v.w;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = ty + 16 * j;
+            const f32x4 v = {tile[4 * tx][c], tile[4 * tx + 1][c], tile[4 * tx + 2][c], tile[4 * tx + 3][c]};
+            *reinterpret_cast<f32x4*>(XT + (size_t)(c0 + c) * m + i0 + 4 * tx) = v;
+        }
+    } else {                                          // ragged edge tile: element by element
+        for (int e = threadIdx.x; e < 64 * 64; e += 256) {
+            const int i = e >> 6, c = e & 63;
+            tile[i][c] = (i0 + i < m && c0 + c < k) ? X[(size_t)(i0 + i) * k + c0 + c] : 0.f;
+        }
+        __syncthreads();
+        for (int e = threadIdx.x; e < 64 * 64; e += 256) {
+            const int c = e >> 6, i = e & 63;
+            if (c0 + c < k && i0 + i < m) XT[(size_t)(c0 + c) * m + i0 + i] = tile[i][c];
+        }
+    }
+}
+
+// One workgroup: the block-row of slot `slot`, 64 rows of X.  Its 4 wavefronts share out the
+// stored blocks of the block-row in contiguous quarters (the paper's concurrent reduction, Section
+// 4.4: several threads share one output's reduction and the partial results are added at the end);
+// each keeps a 64 x 16 partial result, and the partial results are summed through LDS in fixed
+// order.  Per MFMA 16x16x4:
+//   A operand (rows of the result = rows of X): lane l supplies XT[col(p + l/16)][i0 + s*16 + l%16]
+//   B operand (columns = the 16 outputs of the block-row): lane l supplies block_data[p + l/16][l%16]
+//   result: lane l holds rows 4*(l/16) + j (j = 0..3), column l%16
+// A wavefront loads the block-columns and the blocks of U groups of 4 blocks, then issues all
+// 4*U gathers from XT before the first MFMA, so one memory latency covers up to 4*U blocks.
+template <int U>
+__global__ __launch_bounds__(256) void bsr_thin16_f32(const float* __restrict__ XT, const float* __restrict__ data,
+                                                      const int32_t* __restrict__ indices,
+                                                      const int32_t* __restrict__ row_desc, float* __restrict__ Y,
+                                                      int m, int n, int R, int nnzb)
+{
+    constexpr int SUBS = 4;                           // 16-row MFMA tiles per wavefront: 64 rows
+    __shared__ float red[4][64][17];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lo = lane & 15, pp = lane >> 4;
+    const int slot = (int)(blockIdx.x % (unsigned)R);
+    const int i0 = (int)(blockIdx.x / (unsigned)R) * 64;
+    const int32_t* __restrict__ desc = row_desc + (size_t)slot * kRowDescWords;
+    const int r = desc[0];
+    const int p0 = desc[1], nb = desc[2];
+    const unsigned row_bytes = (unsigned)m * 4u;      // one row of XT
+    const int share = ((nb + 3) / 4 + 3) / 4 * 4;     // blocks per wavefront, a multiple of 4
+    const int qb = p0 + min(wave * share, nb), qe = p0 + min((wave + 1) * share, nb);
+
+    f32x4 acc[SUBS];
+#pragma unroll
+    for (int s = 0; s < SUBS; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // Addressing is kept to "uniform base + per-lane 32-bit byte offset + immediate" so that a load
+    // costs at most one vector ALU instruction:
+    //   blocks / block-columns of group u: base(pb) + lane part + u*256 (resp. u*16) bytes
+    //   gather for tile s of group u:      XT + (col*m + i0 + lo)*4 + s*64 bytes
+    // The gather may read up to 63 floats past the m valid entries of an XT row (rows of X past m in
+    // the last tile): that lands in the next XT row, or in the scratch's tail padding for the last
+    // one; those rows of the result are never stored.
+    const unsigned char* xt_bytes = reinterpret_cast<const unsigned char*>(XT);
+    const unsigned char* w_bytes = reinterpret_cast<const unsigned char*>(data);
+    const unsigned char* i_bytes = reinterpret_cast<const unsigned char*>(indices);
+    const unsigned lane_w = (unsigned)(pp * 16 + lo) * 4u, lane_i = (unsigned)pp * 4u;
+    const unsigned lane_x = (unsigned)(i0 + lo) * 4u;
+
+    for (int pb = qb; pb < qe; pb += 4 * U) {
+        float wv[U];
+        int col[U];
+        if (pb + 4 * U <= nnzb) {                     // every block index of the chunk exists
+            const unsigned char* wb = w_bytes + (size_t)pb * 64;
+            const unsigned char* ib = i_bytes + (size_t)pb * 4;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                wv[u] = *reinterpret_cast<const float*>(wb + lane_w + u * 256);
+                col[u] = *reinterpret_cast<const int32_t*>(ib + lane_i + u * 16);
+            }
+        } else {                                      // the last blocks of W: clamp each lane's block index
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int pc = min(pb + 4 * u + pp, qe - 1);
+                wv[u] = data[(size_t)pc * 16 + lo];
+                col[u] = indices[pc];
+            }
+        }
+        if (pb + 4 * U > qe) {                        // chunk reaches past this wavefront's share (uniform)
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (pb + 4 * u + pp >= qe) { wv[u] = 0.f; col[u] = 0; }   // contributes nothing
+        }
+        float xv[U][SUBS];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned off = (unsigned)col[u] * row_bytes + lane_x;
+#pragma unroll
+            for (int s = 0; s < SUBS; ++s) xv[u][s] = *reinterpret_cast<const float*>(xt_bytes + off + s * 64);
+        }
+        // groups past the share multiply zeros (wv = 0, col = 0): no branch around the MFMAs, so the
+        // accumulators stay where they are
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int s = 0; s < SUBS; ++s)
+                acc[s] = __builtin_amdgcn_mfma_f32_16x16x4f32(xv[u][s], wv[u], acc[s], 0, 0, 0);
+    }
+
+#pragma unroll
+    for (int s = 0; s < SUBS; ++s)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) red[wave][s * 16 + 4 * pp + j][lo] = acc[s][j];
+    __syncthreads();
+
+    // thread t: row t/4 of the tile, columns (t%4)*4 .. +3; 4 adjacent lanes write one row's 64 bytes
+    const int row = threadIdx.x >> 2, c4 = (threadIdx.x & 3) * 4;
+    f32x4 sum;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) sum[e] = (red[0][row][c4 + e] + red[1][row][c4 + e]) + (red[2][row][c4 + e] + red[3][row][c4 + e]);
+    if (i0 + row < m) *reinterpret_cast<f32x4*>(Y + (size_t)(i0 + row) * n + (size_t)r * 16 + c4) = sum;
+}
+
+}  // namespace
+
+bool mfma_thin_supports(const bsr_matrix* W) { return W->bs_r == 16 && W->bs_c == 1 && W->dtype == BSR_F32 && W->R > 0; }
+
+size_t mfma_thin_scratch_bytes(const bsr_matrix* W, int64_t m)
+{
+    // m*k floats plus 256 bytes of tail padding (the last tile's gathers may run past the last row)
+    return mfma_thin_supports(W) ? (((size_t)m * (size_t)W->k * sizeof(float) + 256 + 255) & ~(size_t)255) : 0;
+}
+
+bsr_status launch_mfma_thin(const spmm_args& a, const tune_opts& tune)
+{
+    const bsr_matrix* W = a.W;
+    if (!mfma_thin_supports(W) || a.y_dtype != BSR_F32) return BSR_ERR_UNSUPPORTED;
+    const int m = (int)a.m, n = (int)W->n, k = (int)W->k, R = W->R;
+    if (!W->scratch || W->scratch_bytes < mfma_thin_scratch_bytes(W, a.m)) return BSR_ERR_WORKSPACE;
+    if (a.m * W->k >= ((int64_t)1 << 30)) return BSR_ERR_SHAPE;      // byte offsets into XT are 32-bit
+    float* XT = static_cast<float*>(W->scratch);
+    hipLaunchKernelGGL(transpose_f32, dim3((k + 63) / 64, (m + 63) / 64), dim3(256), 0, a.stream,
+                       (const float*)a.X, XT, m, k);
+    if (hipGetLastError() != hipSuccess) return BSR_ERR_HIP;
+    auto go = [&](auto u_tag) -> bsr_status {
+        constexpr int U = decltype(u_tag)::value;
+        const int64_t blocks = (int64_t)((m + 63) / 64) * R;
+        if (blocks >= ((int64_t)1 << 31)) return BSR_ERR_SHAPE;
+        hipLaunchKernelGGL((bsr_thin16_f32<U>), dim3((unsigned)blocks), dim3(256), 0, a.stream,
+                           (const float*)XT, (const float*)W->data, W->indices, W->row_desc, (float*)a.Y, m, n, R,
+                           (int)W->nnzb);
+        return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
+    };
+    // groups of 4 blocks per chunk: a quarter of the longest block-row in one chunk when that is at
+    // most 16 groups (every chunk multiplies all its U groups, so U should not be much larger)
+    int u = tune.a > 0 ? tune.a : ((W->max_row_blocks + 3) / 4 + 3) / 4;
+    if (u <= 4) return go(std::integral_constant<int, 4>{});
+    if (u <= 6) return go(std::integral_constant<int, 6>{});
+    if (u <= 8) return go(std::integral_constant<int, 8>{});
+    if (u <= 10) return go(std::integral_constant<int, 10>{});
+    if (u <= 12) return go(std::integral_constant<int, 12>{});
+    if (u <= 14) return go(std::integral_constant<int, 14>{});
+    if (u <= 16) return go(std::integral_constant<int, 16>{});
+    return go(std::integral_constant<int, 8>{});      // very long block-rows: several chunks of 32 blocks
+}

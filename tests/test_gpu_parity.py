@@ -280,3 +280,41 @@ def test_stripe_kernel_variant(oracle_mod, monkeypatch, extra, dtype, out):
         check(Yg, Yo, So, p.tau, f"stripe{extra} {dtype}->{out} m={m} R={R} C={C}", out_dtype=out)
         Yg2, _ = gpu_product(p, path=MFMA, W=W)
         assert np.array_equal(Yg, Yg2), "two runs differ: race"
+
+
+@pytest.mark.parametrize("u", [0, 4, 8, 16])
+def test_thin_mfma_path(oracle_mod, monkeypatch, u):
+    """16x1 fp32 blocks on the matrix-core path: transposed copy of X in lent scratch, then gather + MFMA."""
+    import paper_2007_13055_amd as lib
+    if u:
+        monkeypatch.setenv("BSR_SPMM_TUNE", f"a={u}")
+    for m, R, C in ((32, 3, 40), (70, 9, 130), (257, 20, 300), (64, 5, 7)):
+        rng = np.random.default_rng(m + R)
+        counts = rng.integers(0, min(C, 90) + 1, size=R)
+        counts[0] = 0
+        counts[-1] = min(C, 77)
+        counts[R // 2] = 1
+        p = wl.make_problem("thin", m, C, R * 16, 16, 1, "f32", "f32", ("counts", counts), ("uniform", 1.0),
+                            ("uniform", 1.0), 500 + m)
+        Yo, So = oracle_of(oracle_mod, p)
+        Yg, W = gpu_product(p, path=MFMA)
+        assert lib.bsr_scratch_size(W, m) >= m * C * 4
+        assert lib.bsr_query_path(W, m) == MFMA
+        check(Yg, Yo, So, p.tau, f"thin mfma m={m} R={R} C={C}")
+        Yw, _ = gpu_product(p, path=WAVE, W=W)
+        check(Yw, Yo, So, p.tau, f"thin wave m={m} R={R} C={C}")
+
+
+def test_thin_mfma_needs_scratch():
+    import torch
+    import paper_2007_13055_amd as lib
+    p = wl.make_problem("thin", 64, 64, 64, 16, 1, "f32", "f32", ("bernoulli", 0.3), ("uniform", 1.0), ("uniform", 1.0), 9)
+    W = lib.bsr_create(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype="f32")
+    assert lib.bsr_query_path(W, 64) == WAVE                      # nothing lent yet: wave path
+    so = lib.load_library()
+    X = to_device(p.X, "f32")
+    Y = torch.empty((64, 64), device="cuda")
+    st = so.bsr_spmm_ex(W.handle, 64, X.data_ptr(), Y.data_ptr(), 0, MFMA, torch.cuda.current_stream().cuda_stream)
+    assert st == 7                                                # BSR_ERR_WORKSPACE
+    W.ensure_scratch(64)
+    assert lib.bsr_query_path(W, 64) == MFMA
