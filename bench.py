@@ -24,7 +24,15 @@ if ROOT not in sys.path:
 # Published MI355X peaks used as roofline ceilings.
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_TFLOPS = {"f32": 157.3, "f16": 2500.0, "bf16": 2500.0}
-HEADLINE = 2
+WORKLOAD_TEXT = {
+    "tiny": "tiny: X fp32 (128,256) U(-1,1); W (256,256) BSR 16x16, Bernoulli(0.25) blocks, U(-1,1); Y fp32",
+    "ffn": "ffn: X fp32 (128,3072) N(0,1); W (3072,3072) BSR 32x32, 922 blocks (density 0.10) uniform without "
+           "replacement, N(0,0.02); Y fp32",
+    "batched": "batched: X bf16 (4096,768) N(0,1); W (3072,768) BSR 16x16, 1843 blocks (density 0.20), N(0,0.02); Y bf16",
+    "thin": "thin: X fp32 (256,4096) U(-1,1); W (4096,4096) BSR 16x1, 52429 blocks (density 0.05), U(-1,1); Y fp32",
+    "skewed": "skewed: X fp16 (8192,8192) N(0,1); W (8192,8192) BSR 64x64, 819 blocks (density 0.05), blocks per "
+              "block-row by rank power law s=1.2; N(0,0.02); Y fp16",
+}
 
 
 def _upload(p):
@@ -88,17 +96,28 @@ def _time_steps(fn, steps, warmup, graph_chunk):
     return wall, e0.elapsed_time(e1) * 1e-3, mode
 
 
+def _measured_traffic(name):
+    """HBM bytes per product from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary (None if absent).
+    A stored measurement of an earlier profiling run of this same command, not something timed here."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+            return json.load(f).get(name)
+    except (OSError, ValueError):
+        return None
+
+
 def _roofline(p, sec_per_launch):
     """Both ceilings for one launch; the binding one is the slower of the two at peak."""
     t_hbm = p.algorithmic_bytes() / (PEAK_HBM_GBS * 1e9)
     t_mfma = p.flops / (PEAK_MFMA_TFLOPS[p.in_dtype] * 1e12)
+    traffic = _measured_traffic(p.name)
     if t_mfma >= t_hbm:
         ach = p.flops / sec_per_launch / 1e12
         return {"bound": "mfma", "achieved": ach, "peak": PEAK_MFMA_TFLOPS[p.in_dtype], "unit": "TFLOP/s",
-                "frac": ach / PEAK_MFMA_TFLOPS[p.in_dtype], "traffic": None}
+                "frac": ach / PEAK_MFMA_TFLOPS[p.in_dtype], "traffic": traffic}
     ach = p.algorithmic_bytes() / sec_per_launch / 1e9
     return {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
-            "traffic": None}
+            "traffic": traffic}
 
 
 def _bench_config(cid, steps, warmup, graph_chunk):
@@ -142,6 +161,12 @@ def main():
                     help="launches per captured HIP graph (0 = plain launches only)")
     ap.add_argument("--no-all-configs", action="store_true", help="skip the per-configuration table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--workload", default="ffn", choices=["tiny", "ffn", "batched", "thin", "skewed"],
+                    help="workload of the headline line (default: the FFN configuration); the others are for "
+                         "profiling one kernel at a time")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="only run 20 device-to-device copies of this many MiB and exit: the reference a "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE reading is scaled by")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the product needs no exchange between GPUs; "
@@ -153,16 +178,27 @@ def main():
     lib.load_library()
     torch.cuda.set_device(0)
     chunk = a.graph_chunk if (a.graph_chunk > 0 and a.steps % a.graph_chunk == 0) else 0
+    if a.copy_calibration > 0:
+        src = torch.ones(a.copy_calibration * (1 << 20) // 4, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(20):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_MiB": a.copy_calibration, "copies": 20}))
+        return
+    headline = {"tiny": 1, "ffn": 2, "batched": 3, "thin": 4, "skewed": 5}[a.workload]
+    if headline == 5:
+        a.steps = min(a.steps, 200)
+        chunk = chunk if a.steps % max(chunk, 1) == 0 else 0
 
-    p, W, r = _bench_config(HEADLINE, a.steps, a.warmup, chunk)
+    p, W, r = _bench_config(headline, a.steps, a.warmup, chunk)
     sec = r["wall_s"] / a.steps
     out = {
         "metric": "effective TFLOP/s of bsr_spmm (2*m*nnzb*bs_r*bs_c per call)",
         "value": p.flops / sec / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "ffn: X fp32 (128,3072) N(0,1); W (3072,3072) BSR 32x32, 922 blocks (density 0.10) "
-                               "uniform without replacement, N(0,0.02); Y fp32",
+        "dtype": "f32" if p.in_dtype == "f32" else p.in_dtype, "data": "synthetic",
+        "config": {"workload": WORKLOAD_TEXT[p.name],
                    "m": p.m, "k": p.k, "n": p.n, "bs_r": p.bs_r, "bs_c": p.bs_c, "nnzb": p.nnzb,
                    "path": r["path"], "launch": r["mode"], "seed": p.seed},
         "roofline": _roofline(p, r["event_s"] / a.steps),
@@ -173,7 +209,7 @@ def main():
 
     if not a.no_all_configs:
         table = {}
-        for cid in (1, 3, 4, 5):
+        for cid in (c for c in (1, 2, 3, 4, 5) if c != headline):
             steps = 200 if cid == 5 else a.steps
             ch = chunk if steps % max(chunk, 1) == 0 else 0
             q, Wq, rq = _bench_config(cid, steps, 20, ch)
