@@ -23,11 +23,20 @@ bsr_status check_shape(int64_t n, int64_t k, int32_t bs_r, int32_t bs_c, int64_t
     return BSR_OK;
 }
 
+size_t item_table_bytes(int64_t R)
+{
+    // the table never holds more than 2*kMaxKsplitItems + 256 descriptors, and a W with R block-rows
+    // has at most kMaxKsplitItems items when the kernel is used at all
+    const size_t items = (size_t)std::min<int64_t>(std::max<int64_t>(R, 1) * 256, 2 * kMaxKsplitItems + 256);
+    return items * kRowDescWords * sizeof(int32_t);
+}
+
 size_t plan_bytes(int64_t R, int64_t nnzb)
 {
     // row order (R int32, padded to 256 B) + row descriptors (16 int32 per block-row) + spare room
     // for per-block work lists; rounded up to 256 bytes
-    size_t b = 128 * (size_t)R + 16 * (size_t)nnzb + 1024;
+    // ... + the k-split kernel's work-item table (up to 2*kMaxKsplitItems + 256 descriptors)
+    size_t b = 128 * (size_t)R + 16 * (size_t)nnzb + 1024 + item_table_bytes(R);
     return (b + 255) & ~(size_t)255;
 }
 
@@ -59,6 +68,60 @@ tune_opts read_tune_env()
         pos = end + 1;
     }
     return t;
+}
+
+// Work-item table of the k-split kernel.
+//
+// The hardware hands workgroup b to XCD b mod 8 and, inside an XCD, round-robin to its CUs, so with
+// every workgroup resident at once workgroup b runs on CU (b mod #CUs) (measured on MI355X).  The
+// (block-row, m-tile) items differ in their number of stored blocks; this places them longest
+// first on the least loaded CU -- all m-tiles of a block-row on one XCD, so the block-row's W
+// blocks are fetched into one L2 only -- and writes the table level by level: entry c + #CUs*level
+// is the level-th item of CU c, or an empty descriptor (block-row -1) that makes the workgroup exit.
+int ksplit_items(const bsr_matrix* W, int tiles, hipStream_t stream)
+{
+    std::lock_guard<std::mutex> lock(W->item_mu);
+    if (W->item_tiles == tiles) return W->item_grid;
+    int n_cu = 0;
+    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, 0) != hipSuccess || n_cu <= 0) n_cu = 256;
+    constexpr int kXcds = 8;
+    if (n_cu % kXcds != 0) return 0;
+    const int R = W->R;
+    std::vector<int64_t> cu_load((size_t)n_cu, 0), xcd_load(kXcds, 0);
+    std::vector<std::vector<int64_t>> lists((size_t)n_cu);       // (slot << 20 | tile) per CU, in placement order
+    for (int s = 0; s < R; ++s) {
+        const int64_t w = std::max<int32_t>(W->slot_blocks[(size_t)s], 1);
+        const int x = (int)(std::min_element(xcd_load.begin(), xcd_load.end()) - xcd_load.begin());
+        for (int t = 0; t < tiles; ++t) {
+            int best = x;
+            for (int c = x; c < n_cu; c += kXcds)
+                if (cu_load[(size_t)c] < cu_load[(size_t)best]) best = c;
+            cu_load[(size_t)best] += w;
+            lists[(size_t)best].push_back(((int64_t)s << 20) | t);
+        }
+        xcd_load[(size_t)x] += w * tiles;
+    }
+    size_t levels = 0;
+    for (const auto& l : lists) levels = std::max(levels, l.size());
+    const size_t grid = levels * (size_t)n_cu;
+    if (grid == 0 || grid > W->item_capacity) return 0;
+    const int32_t* base = W->staging.data() + (W->row_desc - W->row_order);   // host copy of the row descriptors
+    W->item_host.assign(grid * kRowDescWords, 0);
+    for (size_t b = 0; b < grid; ++b) {
+        int32_t* d = W->item_host.data() + b * kRowDescWords;
+        const auto& l = lists[b % (size_t)n_cu];
+        const size_t level = b / (size_t)n_cu;
+        if (level >= l.size()) { d[0] = -1; continue; }
+        const int s = (int)(l[level] >> 20), t = (int)(l[level] & 0xFFFFF);
+        std::memcpy(d, base + (size_t)s * kRowDescWords, sizeof(int32_t) * kRowDescWords);
+        d[3] = t;
+    }
+    if (hipMemcpyAsync(W->item_desc, W->item_host.data(), W->item_host.size() * sizeof(int32_t),
+                       hipMemcpyHostToDevice, stream) != hipSuccess)
+        return 0;
+    W->item_tiles = tiles;
+    W->item_grid = (int)grid;
+    return W->item_grid;
 }
 
 extern "C" {
@@ -135,7 +198,8 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
         d[0] = r;
         d[1] = index_pointer_host[r];
         d[2] = cnt[(size_t)r];
-        for (int j = 0; j < kRowDescCols && j < cnt[(size_t)r]; ++j) d[3 + j] = block_indices_host[d[1] + j];
+        d[3] = 0;
+        for (int j = 0; j < kRowDescCols && j < cnt[(size_t)r]; ++j) d[kRowDescColsAt + j] = block_indices_host[d[1] + j];
     }
     W->max_row_blocks = R ? *std::max_element(cnt.begin(), cnt.end()) : 0;
     W->empty_rows = (int32_t)std::count(cnt.begin(), cnt.end(), 0);
@@ -150,6 +214,13 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
     }
     W->row_order = static_cast<const int32_t*>(workspace_dev);
     W->row_desc = W->row_order + order_words;
+    W->slot_blocks.resize((size_t)R);
+    for (int64_t s = 0; s < R; ++s) W->slot_blocks[(size_t)s] = cnt[(size_t)W->staging[(size_t)s]];
+    {   // the work-item table sits behind the descriptors, 256-byte aligned
+        const size_t used = (sizeof(int32_t) * (order_words + (size_t)R * kRowDescWords) + 255) & ~(size_t)255;
+        W->item_desc = reinterpret_cast<int32_t*>(static_cast<unsigned char*>(workspace_dev) + used);
+        W->item_capacity = item_table_bytes(R) / (kRowDescWords * sizeof(int32_t));
+    }
     if (R > 0) {
         hipError_t e = hipMemcpyAsync(workspace_dev, W->staging.data(),
                                       sizeof(int32_t) * (order_words + (size_t)R * kRowDescWords),

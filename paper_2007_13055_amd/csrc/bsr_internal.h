@@ -5,12 +5,16 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <mutex>
 #include <vector>
 
 #include "bsr_spmm.h"
 
-constexpr int kRowDescWords = 16;                 // int32 per row descriptor (64 bytes)
-constexpr int kRowDescCols = kRowDescWords - 3;   // block-columns held inline
+// Row descriptor (64 bytes): {block-row, first stored block, block count, m-tile, 12 block-columns}.
+constexpr int kRowDescWords = 16;
+constexpr int kRowDescColsAt = 4;                 // word index of the first inline block-column
+constexpr int kRowDescCols = kRowDescWords - kRowDescColsAt;
+constexpr int kMaxKsplitItems = 4096;             // the k-split kernel is used below this many (block-row, m-tile) items
 
 // Host-side description of one W.  Device pointers are borrowed from the caller.
 struct bsr_matrix {
@@ -26,9 +30,18 @@ struct bsr_matrix {
     // Block-rows ordered by stored-block count, longest first; a workgroup's slot s works on
     // block-row row_order[s], so the long rows are dispatched before the short ones.
     const int32_t* row_order = nullptr;      // device, [R]
-    // Per slot, kRowDescWords int32: {block-row, first stored block, block count, the first
-    // kRowDescCols block-columns}: one read starts a workgroup (device, [R][kRowDescWords]).
+    // Per slot, one row descriptor (m-tile word 0): one read starts a workgroup (device, [R][kRowDescWords]).
     const int32_t* row_desc = nullptr;
+    // Work-item table of the k-split kernel (device, in the workspace behind row_desc): one row
+    // descriptor per WORKGROUP with the m-tile filled in, ordered so that the workgroups the
+    // dispatcher puts on one CU carry about the same number of stored blocks (see ksplit_items()).
+    int32_t* item_desc = nullptr;
+    size_t item_capacity = 0;                // descriptors that fit
+    std::vector<int32_t> slot_blocks;        // stored blocks per slot (host)
+    mutable std::mutex item_mu;              // guards the cache below
+    mutable int item_tiles = -1;             // m-tiles the cached table was built for (-1: none)
+    mutable int item_grid = 0;               // workgroups of the cached table
+    mutable std::vector<int32_t> item_host;  // host copy (kept alive for the asynchronous upload)
     int32_t max_row_blocks = 0;              // longest block-row
     int32_t long_rows = 0;                   // leading slots whose block count is > 4x the mean and > 8 ("long" bin)
     int32_t empty_rows = 0;                  // block-rows with no stored block
@@ -69,6 +82,9 @@ bool mfma_supports(const bsr_matrix* W);
 // matrix-core kernel variants (bsr_mfma*.hip)
 bsr_status launch_mfma_direct(const spmm_args& a, const tune_opts& t);
 bsr_status launch_mfma_ksplit(const spmm_args& a, const tune_opts& t);
+// Builds (or reuses) the k-split work-item table for `tiles` m-tiles and queues its upload on `stream`;
+// returns the number of workgroups, 0 if the table does not fit the workspace.
+int ksplit_items(const bsr_matrix* W, int tiles, hipStream_t stream);
 bsr_status launch_mfma_tile(const spmm_args& a, const tune_opts& t);
 bsr_status launch_mfma_stripe(const spmm_args& a, const tune_opts& t);
 bool mfma_stripe_supports(const bsr_matrix* W, int tm);   // 16x16 blocks, 16-bit type, tm rows of X fit in LDS

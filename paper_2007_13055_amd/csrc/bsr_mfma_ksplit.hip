@@ -17,7 +17,7 @@ template <typename T, typename O, int BS_R, int BS_C>
 __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, const T* __restrict__ data,
                                                        const int32_t* __restrict__ indices,
                                                        const int32_t* __restrict__ row_desc, O* __restrict__ Y,
-                                                       int m, int k, int n, int R, int per)
+                                                       int m, int k, int n, int R, int per, int items)
 {
     constexpr int MM = BS_R >= 32 ? 32 : 16;
     constexpr int NA = BS_R / MM;
@@ -32,11 +32,15 @@ __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nw_max = blockDim.x >> 6;
     const int li = lane % MM, h = lane / MM;
-    const int slot = (int)(blockIdx.x % (unsigned)R);
-    const int i_base = (int)(blockIdx.x / (unsigned)R) * MM;
-    // one read of the slot's descriptor: block-row, first stored block, count, first block-columns
-    const int32_t* __restrict__ desc = row_desc + (size_t)slot * kRowDescWords;
+    // one read of the workgroup's descriptor: block-row, first stored block, count, m-tile, first
+    // block-columns.  With a work-item table (items != 0) workgroup b takes entry b -- the table is
+    // laid out so that the workgroups sharing a CU carry about equal work -- and an entry with
+    // block-row -1 is a filler; without one, workgroup b takes slot b mod R of m-tile b div R.
+    const int32_t* __restrict__ desc =
+        row_desc + (size_t)(items ? blockIdx.x : blockIdx.x % (unsigned)R) * kRowDescWords;
     const int r = desc[0];
+    if (r < 0) return;                                // whole workgroup leaves together
+    const int i_base = (items ? desc[3] : (int)(blockIdx.x / (unsigned)R)) * MM;
     const int p0 = desc[1], p1 = p0 + desc[2];
     // wavefronts that take part: about `per` stored blocks each, at most all of the workgroup's;
     // the others go straight to the barrier, so short block-rows cost no loads in idle wavefronts
@@ -54,7 +58,7 @@ __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, 
     Frag<T, CH> wf[2][NA], xf[2];
     auto fetch = [&](int buf, int p) {
         const int j = p - p0;
-        const int c = j < kRowDescCols ? desc[3 + j] : indices[p];
+        const int c = j < kRowDescCols ? desc[kRowDescColsAt + j] : indices[p];
         const T* wp = wbase + (size_t)p * (BS_R * BS_C);
 #pragma unroll
         for (int u = 0; u < NA; ++u) wf[buf][u].load(wp + u * (MM * BS_C));
@@ -120,11 +124,18 @@ bsr_status launch_ksplit_shape(const spmm_args& a, const tune_opts& tune)
     nw = nw < 1 ? 1 : (nw > 8 ? 8 : nw);
     if (tune.nw >= 1 && tune.nw <= 8) nw = tune.nw;
     const int64_t tiles = (m + MM - 1) / MM;
-    const int64_t blocks = tiles * R;
+    int64_t blocks = tiles * R;
     if (blocks >= ((int64_t)1 << 31) || blocks * 64 * nw >= ((int64_t)1 << 32)) return BSR_ERR_SHAPE;
+    // CU-balanced work-item table when there are more items than CUs (else every item has a CU to itself)
+    const int32_t* table = W->row_desc;
+    int items = 0;
+    if (tune.b != 1 && blocks > 256 && blocks <= kMaxKsplitItems) {
+        const int grid = ksplit_items(W, (int)tiles, a.stream);
+        if (grid > 0) { table = W->item_desc; items = 1; blocks = grid; }
+    }
     const size_t lds = (size_t)nw * MM * (BS_R + 4) * sizeof(float);
     hipLaunchKernelGGL((bsr_mfma_ksplit<T, O, BS_R, BS_C>), dim3((unsigned)blocks), dim3(64 * nw), lds, a.stream,
-                       (const T*)a.X, (const T*)W->data, W->indices, W->row_desc, (O*)a.Y, m, k, n, R, per);
+                       (const T*)a.X, (const T*)W->data, W->indices, table, (O*)a.Y, m, k, n, R, per, items);
     return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
 }
 

@@ -167,7 +167,7 @@ __global__ __launch_bounds__(256) void bsr_mfma_tile(const T* __restrict__ X, co
 #pragma unroll
         for (int d = 0; d < D; ++d) {                 // the first D block-columns come from the descriptor
             const int j0 = min(d, p1 - 1 - p0);
-            fetch(d, p0 + d, j0 < kRowDescCols ? desc[3 + j0] : indices[p0 + j0]);
+            fetch(d, p0 + d, j0 < kRowDescCols ? desc[kRowDescColsAt + j0] : indices[p0 + j0]);
         }
         for (int p = p0; p < p1; p += D) {
 #pragma unroll

@@ -318,3 +318,20 @@ def test_thin_mfma_needs_scratch():
     assert st == 7                                                # BSR_ERR_WORKSPACE
     W.ensure_scratch(64)
     assert lib.bsr_query_path(W, 64) == MFMA
+
+
+def test_ksplit_work_item_table_and_m_changes(oracle_mod, monkeypatch):
+    """More (block-row, m-tile) items than CUs: the k-split kernel runs from its CU-balanced work-item
+    table; the table is rebuilt when m changes on the same handle."""
+    monkeypatch.setenv("BSR_SPMM_TUNE", "variant=2")
+    rng = np.random.default_rng(77)
+    R, C, bs = 40, 24, 32
+    counts = rng.integers(0, 21, size=R)
+    counts[3] = 0
+    W = None
+    for m in (330, 1000, 330, 97):                    # 440, 1280, 440 and 160 items (the last without a table)
+        p = wl.make_problem("it", m, C * bs, R * bs, bs, bs, "f32", "f32", ("counts", counts), ("normal", 1.0),
+                            ("normal", 1.0), 600)     # same seed: same pattern and W, X differs in size only
+        Yo, So = oracle_of(oracle_mod, p)
+        Yg, W = gpu_product(p, path=MFMA, W=W)
+        check(Yg, Yo, So, p.tau, f"k-split items m={m}")
