@@ -36,7 +36,9 @@ size_t plan_bytes(int64_t R, int64_t nnzb)
     // row order (R int32, padded to 256 B) + row descriptors (16 int32 per block-row) + spare room
     // for per-block work lists; rounded up to 256 bytes
     // ... + the k-split kernel's work-item table (up to 2*kMaxKsplitItems + 256 descriptors)
-    size_t b = 128 * (size_t)R + 16 * (size_t)nnzb + 1024 + item_table_bytes(R);
+    // (row order 4R + descriptors 64R + pair pointers 4R + pair entries: 16 bytes each, at most
+    // nnzb/2 + kStripeChunkPairs per block-row; each part padded to 256 B)
+    size_t b = (72 + 16 * (size_t)kStripeChunkPairs + 16) * (size_t)R + 8 * (size_t)nnzb + 2048 + item_table_bytes(R);
     return (b + 255) & ~(size_t)255;
 }
 
@@ -185,7 +187,7 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
     std::vector<int32_t> cnt((size_t)R);
     for (int64_t r = 0; r < R; ++r) cnt[(size_t)r] = index_pointer_host[r + 1] - index_pointer_host[r];
     const size_t order_words = (((size_t)R * 4 + 255) & ~(size_t)255) / 4;   // row_order, padded to 256 B
-    W->staging.assign(order_words + (size_t)R * kRowDescWords + 1, 0);
+    W->staging.assign(order_words + (size_t)R * kRowDescWords + 64, 0);
     std::iota(W->staging.begin(), W->staging.begin() + R, 0);
     std::stable_sort(W->staging.begin(), W->staging.begin() + R,
                      [&](int32_t a, int32_t b) { return cnt[(size_t)a] > cnt[(size_t)b]; });
@@ -216,14 +218,53 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
     W->row_desc = W->row_order + order_words;
     W->slot_blocks.resize((size_t)R);
     for (int64_t s = 0; s < R; ++s) W->slot_blocks[(size_t)s] = cnt[(size_t)W->staging[(size_t)s]];
-    {   // the work-item table sits behind the descriptors, 256-byte aligned
-        const size_t used = (sizeof(int32_t) * (order_words + (size_t)R * kRowDescWords) + 255) & ~(size_t)255;
-        W->item_desc = reinterpret_cast<int32_t*>(static_cast<unsigned char*>(workspace_dev) + used);
+
+    // Pair table (16x16 blocks only; the stripe kernel multiplies two stored blocks of a block-row per
+    // MFMA).  Per block-row, in natural order, its stored blocks two by two, and the row's list
+    // filled up to a whole number of chunks of kStripeChunkPairs entries (an empty row has none).
+    // An entry is {byte offset of the first block in block_data, byte offset of the second, first
+    // block-column, second block-column}; a slot with no block ("dead") has offset 2^31 -- past the
+    // end of W, read as zeros -- and block-column C, the kernel's all-zero panel.  pair_ptr[r] is
+    // the first entry of block-row r.  Left out when W has 2 GiB of blocks or more.
+    size_t words = order_words + (size_t)R * kRowDescWords;
+    words = (words + 63) & ~(size_t)63;
+    if (bs_r == 16 && bs_c == 16 && nnzb * 512 < ((int64_t)1 << 31)) {
+        const size_t ptr_at = words;
+        const size_t ptr_words = ((size_t)R + 1 + 63) & ~(size_t)63;
+        constexpr int KP = kStripeChunkPairs;
+        size_t n_entries = 0;
+        for (int64_t r = 0; r < R; ++r) n_entries += ((size_t)(cnt[(size_t)r] + 1) / 2 + KP - 1) / KP * KP;
+        W->staging.resize(ptr_at + ptr_words + 4 * n_entries + 64, 0);
+        int32_t* ptr = W->staging.data() + ptr_at;
+        int32_t* pr = ptr + ptr_words;
+        const int32_t dead_off = INT32_MIN, dead_col = (int32_t)(k / bs_c);
+        size_t q = 0;
+        for (int64_t r = 0; r < R; ++r) {
+            ptr[r] = (int32_t)q;
+            const size_t row_first = q;
+            for (int32_t p = index_pointer_host[r]; p < index_pointer_host[r + 1]; p += 2, ++q) {
+                const bool two = p + 1 < index_pointer_host[r + 1];
+                pr[4 * q] = p * 512;
+                pr[4 * q + 1] = two ? (p + 1) * 512 : dead_off;
+                pr[4 * q + 2] = block_indices_host[p];
+                pr[4 * q + 3] = two ? block_indices_host[p + 1] : dead_col;
+            }
+            for (; (q - row_first) % KP != 0; ++q) {
+                pr[4 * q] = pr[4 * q + 1] = dead_off;
+                pr[4 * q + 2] = pr[4 * q + 3] = dead_col;
+            }
+        }
+        ptr[R] = (int32_t)q;
+        W->pair_ptr = W->row_order + ptr_at;
+        W->pairs = W->pair_ptr + ptr_words;
+        words = (ptr_at + ptr_words + 4 * n_entries + 63) & ~(size_t)63;
+    }
+    {   // the work-item table sits behind everything else, 256-byte aligned
+        W->item_desc = const_cast<int32_t*>(W->row_order) + words;
         W->item_capacity = item_table_bytes(R) / (kRowDescWords * sizeof(int32_t));
     }
     if (R > 0) {
-        hipError_t e = hipMemcpyAsync(workspace_dev, W->staging.data(),
-                                      sizeof(int32_t) * (order_words + (size_t)R * kRowDescWords),
+        hipError_t e = hipMemcpyAsync(workspace_dev, W->staging.data(), sizeof(int32_t) * words,
                                       hipMemcpyHostToDevice, (hipStream_t)hip_stream);
         if (e != hipSuccess) { delete W; return BSR_ERR_HIP; }
     }

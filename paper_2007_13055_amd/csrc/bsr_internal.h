@@ -15,6 +15,7 @@ constexpr int kRowDescWords = 16;
 constexpr int kRowDescColsAt = 4;                 // word index of the first inline block-column
 constexpr int kRowDescCols = kRowDescWords - kRowDescColsAt;
 constexpr int kMaxKsplitItems = 4096;             // the k-split kernel is used below this many (block-row, m-tile) items
+constexpr int kStripeChunkPairs = 6;              // the stripe kernel's pair table lists block-rows in chunks of this many pairs
 
 // Host-side description of one W.  Device pointers are borrowed from the caller.
 struct bsr_matrix {
@@ -35,6 +36,9 @@ struct bsr_matrix {
     // Work-item table of the k-split kernel (device, in the workspace behind row_desc): one row
     // descriptor per WORKGROUP with the m-tile filled in, ordered so that the workgroups the
     // dispatcher puts on one CU carry about the same number of stored blocks (see ksplit_items()).
+    // Pair table of the stripe kernel (16x16 blocks): pair_ptr[R+1], pairs[entries][4] (see bsr_create).
+    const int32_t* pair_ptr = nullptr;
+    const int32_t* pairs = nullptr;
     int32_t* item_desc = nullptr;
     size_t item_capacity = 0;                // descriptors that fit
     std::vector<int32_t> slot_blocks;        // stored blocks per slot (host)

@@ -9,9 +9,18 @@
 // Work split: the grid is (m-tiles) x (groups of consecutive block-rows); inside a workgroup
 // every wavefront owns 4 consecutive block-rows (64 columns of Y = one 128-byte line of bf16 per
 // row) for all TM rows.  Two stored blocks of a block-row are multiplied per MFMA: the 16x16x32
-// instruction takes k = 32, lanes 0-31 supply block p and lanes 32-63 block p+1 (an odd last
-// block is paired with zeros).  W blocks stream from global memory into registers, a block-row
-// ahead of the arithmetic; X operands come from the LDS stripe at the column block_indices names.
+// instruction takes k = 32, lanes 0-31 supply block p and lanes 32-63 block p+1.
+//
+// The arithmetic has no data-dependent branches.  The plan's pair table lists every block-row as
+// whole CHUNKS of kStripeChunkPairs pairs; a slot without a stored block ("dead") carries a byte
+// offset past the end of W, which a buffer load answers with zeros, and the index of an extra,
+// all-zero LDS panel for X.  So a chunk is always kStripeChunkPairs x (TM/16) MFMAs, the
+// compiler can schedule its LDS reads and MFMAs freely, and W for the next two block-rows is
+// already on its way (three register buffers) while one is multiplied.
+//
+// LDS layout of the stripe: one PANEL per block-column (TM rows x 32 bytes, panels PS bytes apart),
+// so the 16-row tiles of a lane's operand are at compile-time offsets from one address; the two
+// 16-byte halves of a row are swapped in rows with bit 2 set.
 #include "bsr_mfma_common.h"
 
 using namespace bsr_dev;
@@ -20,23 +29,30 @@ namespace {
 
 constexpr int kXcds = 8;
 constexpr int kRowsPerWave = 4;      // block-rows per wavefront: 4 x 16 columns = 64 outputs per row of Y
-constexpr int kPairs = 8;            // pairs of blocks held in registers per block-row chunk
+constexpr int KP = kStripeChunkPairs;
+constexpr int kBufs = 3;             // W chunks in registers: one in use, two in flight
+constexpr int kStageBatch = 8;       // 16-byte loads in flight per thread while the stripe is staged
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 template <typename T, typename O, int TM>
 __global__ __launch_bounds__(768) void bsr_mfma_stripe16(const T* __restrict__ X, const T* __restrict__ data,
-                                                          const int32_t* __restrict__ indices,
-                                                          const int32_t* __restrict__ indptr, O* __restrict__ Y,
-                                                          int m, int k, int n, int R, int n_tiles, int n_groups,
-                                                          int rows_per_group, unsigned cpr_magic, int nnzb)
+                                                         unsigned w_bytes, const int32_t* __restrict__ pair_ptr,
+                                                         const i32x4* __restrict__ pairs, O* __restrict__ Y,
+                                                         int m, int k, int n, int R, int n_tiles, int n_groups,
+                                                         int rows_per_group, unsigned cpr_magic)
 {
     constexpr int SUB = TM / 16;                      // 16-row MFMA tiles along m
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];   // [TM][k*2 + 16]
-    const int RB = k * (int)sizeof(T), RS = RB + 16;  // row bytes, padded LDS stride (rows shift by 4 banks)
+    constexpr int PS = TM * 32 + 32;                  // bytes from one panel to the next (+32: panels shift by 8 banks)
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];   // [k/16 + 1 panels][PS], then per-wavefront scratch
+    const int RB = k * (int)sizeof(T);                // bytes of one row of X
+    const int C = k / 16;                             // block-columns; panel C is the all-zero one
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, h = lane >> 4;          // MFMA row/column index, k-group 0..3
-    const int half = h >> 1;                          // which block of the pair this lane feeds
+    const bool second = h >= 2;                       // this lane feeds the second block of a pair
+    const int hh = h & 1;                             // which 8 of the block's 16 columns
 
     // workgroup -> (m-tile, block-row group); the groups of one m-tile share an XCD (and its L2 copy
     // of the stripe)
@@ -48,71 +64,68 @@ __global__ __launch_bounds__(768) void bsr_mfma_stripe16(const T* __restrict__ X
     const int r_first = group * rows_per_group + wave * kRowsPerWave;
     const int r_end = min(min((group + 1) * rows_per_group, R), r_first + kRowsPerWave);
 
-    // lane's part of a pair: block p+half, row li of the block, 8 columns starting at (h&1)*8
-    const unsigned char* wlane = reinterpret_cast<const unsigned char*>(data) + half * 512 + li * 32 + (h & 1) * 16;
-    const int32_t* ilane = indices + half;
-    const unsigned char* xlane = lds + (size_t)li * RS + (h & 1) * 16;
-
-    // stored-block ranges of this wavefront's block-rows (rows past r_end get an empty range)
-    int pb0[kRowsPerWave], pb1[kRowsPerWave];
+    // entry ranges of this wavefront's block-rows in the pair table, whole chunks each (rows past
+    // r_end get an empty range)
+    int q0[kRowsPerWave], q1[kRowsPerWave];
 #pragma unroll
     for (int j = 0; j < kRowsPerWave; ++j) {
         const int r = min(r_first + j, R - 1);
-        pb0[j] = indptr[r];
-        pb1[j] = r_first + j < r_end ? indptr[r + 1] : pb0[j];
+        q0[j] = pair_ptr[r];
+        q1[j] = r_first + j < r_end ? pair_ptr[r + 1] : q0[j];
     }
 
-    // A chunk = up to kPairs pairs of blocks of one block-row: W operands and block-columns, all
-    // loads independent of each other.  Two chunk buffers: the next block-row's chunk is loaded
-    // while the current one is multiplied.
-    u32x4 wreg[2][kPairs];
-    int col[2][kPairs];
-    auto load_chunk = [&](int buf, int pb, int p1) {
-        if (pb >= p1) return;                         // uniform: empty block-row or past its end
-        if (pb + 2 * kPairs <= nnzb) {
-            // every block index of the chunk exists (blocks past p1 belong to later block-rows and
-            // are discarded below): plain base + q*1024 addressing, no per-lane clamping
-            const unsigned char* wb = wlane + (size_t)pb * 512;
-            const int32_t* ib = ilane + pb;
+    // W through a buffer resource: a byte offset >= w_bytes (the dead slots) reads as zero
+    const __amdgpu_buffer_rsrc_t wrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(data), 0, (int)w_bytes, 0x00020000);
+    // lane's part of a block: row li, 8 columns starting at hh*8
+    const unsigned lane_w = (unsigned)(li * 32 + hh * 16);
+    const unsigned lane_x = (unsigned)(li * 32 + ((hh ^ ((li >> 2) & 1)) * 16));
+
+    u32x4 wreg[kBufs][KP];
+    unsigned xoff[kBufs][KP];                         // LDS byte offset of the lane's X operand, 16-row tile 0
+    auto load_chunk = [&](int buf, int qb) {          // pair entries qb .. qb+KP-1: {offset 1, offset 2, column 1, column 2}
+        i32x4 e[KP];
 #pragma unroll
-            for (int q = 0; q < kPairs; ++q) {
-                wreg[buf][q] = *reinterpret_cast<const u32x4*>(wb + q * 1024);
-                col[buf][q] = ib[2 * q];
-            }
-        } else {                                      // the last blocks of W: clamp each lane's block index
+        for (int q = 0; q < KP; ++q) e[q] = pairs[qb + q];
 #pragma unroll
-            for (int q = 0; q < kPairs; ++q) {
-                const int pc = min(pb + 2 * q + half, p1 - 1) - half;
-                wreg[buf][q] = *reinterpret_cast<const u32x4*>(wlane + (size_t)pc * 512);
-                col[buf][q] = ilane[pc];
-            }
+        for (int q = 0; q < KP; ++q) {
+            const unsigned off = (unsigned)(second ? e[q].y : e[q].x) + lane_w;
+            wreg[buf][q] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)off, 0, 0);
+            xoff[buf][q] = (unsigned)(second ? e[q].w : e[q].z) * PS + lane_x;
         }
-#pragma unroll
-        for (int q = 0; q < kPairs; ++q)              // odd tail / past the end of the block-row: zeros
-            if (pb + 2 * q + 2 > p1 && pb + 2 * q + half >= p1) { wreg[buf][q] = u32x4{0u, 0u, 0u, 0u}; col[buf][q] = 0; }
     };
 
-    load_chunk(0, pb0[0], pb1[0]);                    // in flight while the stripe is staged
+    // first chunks of the first block-rows: in flight while the stripe is staged
+#pragma unroll
+    for (int j = 0; j < kBufs && j < kRowsPerWave; ++j)
+        if (q0[j] < q1[j]) load_chunk(j, q0[j]);      // uniform
 
     // ---- stage the stripe: TM rows x k columns, one contiguous piece of memory ----
     // chunk q (16 bytes) of the stripe lies in row q / cpr; the quotient comes from a multiply with
-    // cpr_magic = floor(2^32 / cpr) + 1, exact for q < 2^16 (the stripe has at most 10240 chunks)
+    // cpr_magic = floor(2^32 / cpr) + 1, exact for q < 2^16 (the stripe has at most 10240 chunks).
+    // kStageBatch loads are issued before the first LDS write; past the end the last chunk is
+    // simply copied again (same bytes to the same place).
     {
-        const int cpr = RB / 16;                      // 16-byte chunks per row
+        const int cpr = RB / 16;                      // 16-byte chunks per row: 2 per block-column
         const int total = TM * cpr;
         const unsigned char* xb = reinterpret_cast<const unsigned char*>(X) + (size_t)i_base * (size_t)RB;
-        if (i_base + TM <= m) {                       // whole tile inside X (uniform)
-            for (int q = tid; q < total; q += blockDim.x) {
-                const int row = (int)__umulhi((unsigned)q, cpr_magic);
-                *reinterpret_cast<u32x4*>(lds + (size_t)(q + row) * 16) = *reinterpret_cast<const u32x4*>(xb + (size_t)q * 16);
-            }
-        } else {                                      // last tile: rows past m repeat row m-1, never stored
-            for (int q = tid; q < total; q += blockDim.x) {
+        const bool whole = i_base + TM <= m;          // uniform; else rows past m repeat row m-1, never stored
+        const int step = (int)blockDim.x;
+        for (int base = tid; base < total; base += kStageBatch * step) {
+            u32x4 v[kStageBatch];
+            int dst[kStageBatch];
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) {
+                const int q = min(base + u * step, total - 1);
                 const int row = (int)__umulhi((unsigned)q, cpr_magic), cc = q - row * cpr;
-                const size_t src = (size_t)min(row, m - 1 - i_base) * (size_t)RB + (size_t)cc * 16;
-                *reinterpret_cast<u32x4*>(lds + (size_t)(q + row) * 16) = *reinterpret_cast<const u32x4*>(xb + src);
+                const size_t src = whole ? (size_t)q * 16 : (size_t)min(row, m - 1 - i_base) * (size_t)RB + (size_t)cc * 16;
+                dst[u] = (cc >> 1) * PS + row * 32 + (((cc & 1) ^ ((row >> 2) & 1)) * 16);
+                v[u] = *reinterpret_cast<const u32x4*>(xb + src);
             }
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) *reinterpret_cast<u32x4*>(lds + dst[u]) = v[u];
         }
+        for (int z = tid; z < TM * 2; z += step) *reinterpret_cast<u32x4*>(lds + C * PS + z * 16) = u32x4{0u, 0u, 0u, 0u};
     }
     __syncthreads();
     if (r_first >= r_end) return;                     // no barrier after this point
@@ -123,32 +136,31 @@ __global__ __launch_bounds__(768) void bsr_mfma_stripe16(const T* __restrict__ X
 #pragma unroll
         for (int s = 0; s < SUB; ++s) acc[j][s] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const unsigned char* xsub[SUB];                   // the lane's row of each 16-row tile of the stripe
+    auto compute_chunk = [&](int buf, int j) {
 #pragma unroll
-    for (int s = 0; s < SUB; ++s) xsub[s] = xlane + (size_t)s * 16 * RS;
-    auto compute_chunk = [&](int buf, int j, int pb, int p1) {
+        for (int q = 0; q < KP; ++q) {
+            Frag<T, 8> wf, xf;
+            wf.w[0] = wreg[buf][q].x; wf.w[1] = wreg[buf][q].y; wf.w[2] = wreg[buf][q].z; wf.w[3] = wreg[buf][q].w;
+            const unsigned char* xp = lds + xoff[buf][q];
 #pragma unroll
-        for (int q = 0; q < kPairs; ++q) {
-            if (pb + 2 * q < p1) {                    // uniform
-                Frag<T, 8> wf, xf;
-                wf.w[0] = wreg[buf][q].x; wf.w[1] = wreg[buf][q].y; wf.w[2] = wreg[buf][q].z; wf.w[3] = wreg[buf][q].w;
-#pragma unroll
-                for (int s = 0; s < SUB; ++s) {
-                    xf.load(reinterpret_cast<const T*>(xsub[s] + col[buf][q] * 32));
-                    mfma_frag<T, 16, 8>(acc[j][s], wf, xf);
-                }
+            for (int s = 0; s < SUB; ++s) {
+                xf.load(reinterpret_cast<const T*>(xp + s * 512));
+                mfma_frag<T, 16, 8>(acc[j][s], wf, xf);
             }
         }
     };
 
 #pragma unroll
     for (int j = 0; j < kRowsPerWave; ++j) {
-        if (j + 1 < kRowsPerWave) load_chunk((j + 1) & 1, pb0[j + 1], pb1[j + 1]);
-        compute_chunk(j & 1, j, pb0[j], pb1[j]);
-        for (int pb = pb0[j] + 2 * kPairs; pb < pb1[j]; pb += 2 * kPairs) {   // block-rows longer than one chunk
-            load_chunk(j & 1, pb, pb1[j]);
-            compute_chunk(j & 1, j, pb, pb1[j]);
+        const int buf = j % kBufs;
+        if (q0[j] < q1[j]) {                          // uniform: the block-row stores something
+            compute_chunk(buf, j);
+            for (int qb = q0[j] + KP; qb < q1[j]; qb += KP) {      // block-rows longer than one chunk
+                load_chunk(buf, qb);
+                compute_chunk(buf, j);
+            }
         }
+        if (j + kBufs < kRowsPerWave && q0[j + kBufs] < q1[j + kBufs]) load_chunk(buf, q0[j + kBufs]);
     }
 
     // Epilogue.  A lane holds, for row i = s*16 + li, columns (r_first + j)*16 + 4h .. +3: neighbouring
@@ -160,7 +172,7 @@ __global__ __launch_bounds__(768) void bsr_mfma_stripe16(const T* __restrict__ X
     constexpr int OS = OB + 16, OC = OB / 16;                // padded LDS stride, 16-byte pieces per row
     constexpr int SPP = sizeof(O) == 2 ? (SUB >= 2 ? 2 : 1) : 1;   // 16-row tiles per pass (scratch <= 4.6 KB)
     constexpr int RPI = 64 / OC;                             // rows one store instruction covers
-    unsigned char* scratch = lds + (size_t)TM * RS + (size_t)wave * (SPP * 16 * OS);
+    unsigned char* scratch = lds + (size_t)(C + 1) * PS + (size_t)wave * (SPP * 16 * OS);
     unsigned char* ybytes = reinterpret_cast<unsigned char*>(Y + (size_t)r_first * 16);
     const int orow = lane / OC, opiece = lane - orow * OC;
     const int valid_bytes = (r_end - r_first) * 16 * (int)sizeof(O);   // the group's last wavefront may own < 4 block-rows
@@ -184,6 +196,13 @@ __global__ __launch_bounds__(768) void bsr_mfma_stripe16(const T* __restrict__ X
     }
 }
 
+size_t stripe_lds_bytes(int k, int tm, int waves, size_t out_size)
+{
+    const size_t panels = (size_t)(k / 16 + 1) * (size_t)(tm * 32 + 32);
+    const int spp = out_size == 2 ? (tm >= 32 ? 2 : 1) : 1;
+    return panels + (size_t)waves * (size_t)spp * 16 * (kRowsPerWave * 16 * out_size + 16);
+}
+
 template <typename T, typename O>
 bsr_status launch_stripe_types(const spmm_args& a, const tune_opts& tune)
 {
@@ -191,9 +210,6 @@ bsr_status launch_stripe_types(const spmm_args& a, const tune_opts& tune)
     const int m = (int)a.m, n = (int)W->n, k = (int)W->k, R = W->R;
     auto go = [&](auto tm_tag) -> bsr_status {
         constexpr int TM = decltype(tm_tag)::value;
-        const size_t lds_stripe = (size_t)TM * ((size_t)k * sizeof(T) + 16);
-        constexpr int SPP = sizeof(O) == 2 ? (TM >= 32 ? 2 : 1) : 1;
-        const size_t scratch_per_wave = (size_t)SPP * 16 * (kRowsPerWave * 16 * sizeof(O) + 16);
         const int n_tiles = (m + TM - 1) / TM;
         // groups of block-rows: enough workgroups for every CU, at most 12 wavefronts (48 block-rows) each
         int n_groups = tune.a > 0 ? tune.a : (256 + n_tiles - 1) / n_tiles;
@@ -204,7 +220,7 @@ bsr_status launch_stripe_types(const spmm_args& a, const tune_opts& tune)
         rows_per_group = (rows_per_group + kRowsPerWave - 1) / kRowsPerWave * kRowsPerWave;
         n_groups = (R + rows_per_group - 1) / rows_per_group;
         const int waves = rows_per_group / kRowsPerWave;
-        const size_t lds = lds_stripe + (size_t)waves * scratch_per_wave;
+        const size_t lds = stripe_lds_bytes(k, TM, waves, sizeof(O));
         if (lds > 160 * 1024) return BSR_ERR_UNSUPPORTED;
         const int64_t blocks = (int64_t)((n_tiles + kXcds - 1) / kXcds) * kXcds * n_groups;
         if (blocks >= ((int64_t)1 << 31)) return BSR_ERR_SHAPE;
@@ -213,8 +229,9 @@ bsr_status launch_stripe_types(const spmm_args& a, const tune_opts& tune)
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (attr != hipSuccess) return BSR_ERR_HIP;
         hipLaunchKernelGGL((bsr_mfma_stripe16<T, O, TM>), dim3((unsigned)blocks), dim3(64 * waves), lds, a.stream,
-                           (const T*)a.X, (const T*)W->data, W->indices, W->indptr, (O*)a.Y, m, k, n, R, n_tiles,
-                           n_groups, rows_per_group, (unsigned)(0x100000000ull / (unsigned)(k * sizeof(T) / 16)) + 1u, (int)W->nnzb);
+                           (const T*)a.X, (const T*)W->data, (unsigned)(W->nnzb * 512), W->pair_ptr,
+                           reinterpret_cast<const i32x4*>(W->pairs), (O*)a.Y, m, k, n, R, n_tiles,
+                           n_groups, rows_per_group, (unsigned)(0x100000000ull / (unsigned)(k * sizeof(T) / 16)) + 1u);
         return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
     };
     const int tm = tune.mt > 0 ? tune.mt * 16 : 64;
@@ -228,13 +245,15 @@ bsr_status launch_stripe_types(const spmm_args& a, const tune_opts& tune)
 bool mfma_stripe_supports(const bsr_matrix* W, int tm)
 {
     if (W->bs_r != 16 || W->bs_c != 16 || W->dtype == BSR_F32) return false;
-    return (size_t)tm * ((size_t)W->k * 2 + 16) + 12 * 16 * (kRowsPerWave * 16 * 4 + 16) <= 160 * 1024;
+    // byte offsets into W are 32-bit with the top bit marking a dead slot; the stripe has < 2^16 chunks
+    if (!W->pairs || W->nnzb * 512 >= ((int64_t)1 << 31) || (int64_t)tm * (W->k / 8) >= 65536) return false;
+    return stripe_lds_bytes((int)W->k, tm, 12, 4) <= 160 * 1024;
 }
 
 bsr_status launch_mfma_stripe(const spmm_args& a, const tune_opts& t)
 {
     const bsr_matrix* W = a.W;
-    if (W->bs_r != 16 || W->bs_c != 16) return BSR_ERR_UNSUPPORTED;
+    if (!mfma_stripe_supports(W, 16)) return BSR_ERR_UNSUPPORTED;
     if (W->dtype == BSR_F16) return a.y_dtype == BSR_F32 ? launch_stripe_types<_Float16, float>(a, t)
                                                          : launch_stripe_types<_Float16, _Float16>(a, t);
     if (W->dtype == BSR_BF16) return a.y_dtype == BSR_F32 ? launch_stripe_types<__bf16, float>(a, t)

@@ -18,35 +18,41 @@ using namespace bsr_dev;
 
 namespace {
 
-// XT[c][i] = X[i][c]; 64x64 tiles through LDS, 16 bytes per lane on both sides.
+// XT[c][i] = X[i][c]; tiles of 32 rows x 64 columns of X through LDS, 16 bytes per lane on both sides.
 __global__ __launch_bounds__(256) void transpose_f32(const float* __restrict__ X, float* __restrict__ XT, int m, int k)
 {
-    __shared__ float tile[64][65];
-    const int c0 = blockIdx.x * 64, i0 = blockIdx.y * 64;
-    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;       // 16 x 16
-    const bool full = c0 + 64 <= k && i0 + 64 <= m && (k & 3) == 0 && (m & 3) == 0;
+    constexpr int TI = 32, TC = 64;
+    __shared__ float tile[TI][TC + 1];
+    const int c0 = blockIdx.x * TC, i0 = blockIdx.y * TI;
+    const bool full = c0 + TC <= k && i0 + TI <= m && (k & 3) == 0 && (m & 3) == 0;
     if (full) {
+        {   // read: 16 lanes cover one row's 64 columns
+            const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int i = ty + 16 * j;
-            const f32x4 v = *reinterpret_cast<const f32x4*>(X + (size_t)(i0 + i) * k + c0 + 4 * tx);
-            tile[i][4 * tx] = v.x; tile[i][4 * tx + 1] = v.y; tile[i][4 * tx + 2] = v.z; tile[i][4 * tx + 3] = v.w;
+            for (int j = 0; j < TI / 16; ++j) {
+                const int i = ty + 16 * j;
+                const f32x4 v = *reinterpret_cast<const f32x4*>(X + (size_t)(i0 + i) * k + c0 + 4 * tx);
+                tile[i][4 * tx] = v.x; tile[i][4 * tx + 1] = v.y; tile[i][4 * tx + 2] = v.z; tile[i][4 * tx + 3] = v.w;
+            }
         }
         __syncthreads();
+        {   // write: 8 lanes cover one XT row's 32 entries
+            const int tx = threadIdx.x & 7, ty = threadIdx.x >> 3;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int c = ty + 16 * j;
-            const f32x4 v = {tile[4 * tx][c], tile[4 * tx + 1][c], tile[4 * tx + 2][c], tile[4 * tx + 3][c]};
-            *reinterpret_cast<f32x4*>(XT + (size_t)(c0 + c) * m + i0 + 4 * tx) = v;
+            for (int j = 0; j < TC / 32; ++j) {
+                const int c = ty + 32 * j;
+                const f32x4 v = {tile[4 * tx][c], tile[4 * tx + 1][c], tile[4 * tx + 2][c], tile[4 * tx + 3][c]};
+                *reinterpret_cast<f32x4*>(XT + (size_t)(c0 + c) * m + i0 + 4 * tx) = v;
+            }
         }
     } else {                                          // ragged edge tile: element by element
-        for (int e = threadIdx.x; e < 64 * 64; e += 256) {
-            const int i = e >> 6, c = e & 63;
+        for (int e = threadIdx.x; e < TI * TC; e += 256) {
+            const int i = e / TC, c = e % TC;
             tile[i][c] = (i0 + i < m && c0 + c < k) ? X[(size_t)(i0 + i) * k + c0 + c] : 0.f;
         }
         __syncthreads();
-        for (int e = threadIdx.x; e < 64 * 64; e += 256) {
-            const int c = e >> 6, i = e & 63;
+        for (int e = threadIdx.x; e < TI * TC; e += 256) {
+            const int c = e / TI, i = e % TI;
             if (c0 + c < k && i0 + i < m) XT[(size_t)(c0 + c) * m + i0 + i] = tile[i][c];
         }
     }
@@ -171,7 +177,7 @@ bsr_status launch_mfma_thin(const spmm_args& a, const tune_opts& tune)
     if (!W->scratch || W->scratch_bytes < mfma_thin_scratch_bytes(W, a.m)) return BSR_ERR_WORKSPACE;
     if (a.m * W->k >= ((int64_t)1 << 30)) return BSR_ERR_SHAPE;      // byte offsets into XT are 32-bit
     float* XT = static_cast<float*>(W->scratch);
-    hipLaunchKernelGGL(transpose_f32, dim3((k + 63) / 64, (m + 63) / 64), dim3(256), 0, a.stream,
+    hipLaunchKernelGGL(transpose_f32, dim3((k + 63) / 64, (m + 31) / 32), dim3(256), 0, a.stream,
                        (const float*)a.X, XT, m, k);
     if (hipGetLastError() != hipSuccess) return BSR_ERR_HIP;
     auto go = [&](auto u_tag) -> bsr_status {

@@ -20,12 +20,19 @@ using namespace bsr_dev;
 namespace {
 
 constexpr int kXcds = 8;
+constexpr int kMaxGroups = 8;
+
+// Slot ranges [start[g], start[g+1]) of the launch-order groups (passed by value as a kernel argument).
+struct slot_groups {
+    int n;
+    int start[kMaxGroups + 1];
+};
 
 template <typename T, typename O, int BS_R, int BS_C, int MT, int D>
 __global__ __launch_bounds__(256) void bsr_mfma_tile(const T* __restrict__ X, const T* __restrict__ data,
                                                      const int32_t* __restrict__ indices,
                                                      const int32_t* __restrict__ row_desc, O* __restrict__ Y,
-                                                     int m, int k, int n, int R, int n_tiles, int n_long)
+                                                     int m, int k, int n, int R, int n_tiles, slot_groups groups)
 {
     constexpr int MM = 32;                            // MFMA tile edge (bs_r >= 32 only)
     constexpr int NA = BS_R / MM;
@@ -43,20 +50,27 @@ __global__ __launch_bounds__(256) void bsr_mfma_tile(const T* __restrict__ X, co
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, h = lane >> 5;
 
-    // Workgroup -> (slot, m-tile).  XCD x owns m-tiles x, x+8, ...  Its first workgroups are the
-    // n_long longest block-rows of ALL its m-tiles (they run longest, so they must start first or
-    // the last m-tile's long rows would run on alone at the end); then, m-tile after m-tile, the
-    // other block-rows, still longest first.
+    // Workgroup -> (slot, m-tile).  XCD x owns m-tiles x, x+8, ...  The slots (block-rows, longest
+    // first) are cut into groups; the XCD works through group after group, and inside a group
+    // through its m-tiles one after the other.  Group 0 holds the few very long block-rows: they
+    // run longest, so they start first for all m-tiles (otherwise the last m-tile's long rows
+    // would run on alone at the end).  The other groups are sized so that a group's W blocks stay
+    // in the XCD's L2 while its m-tiles pass: W is then fetched from memory once per group and
+    // XCD instead of once per m-tile, at the price of re-reading the X stripe once per group.
     const int xcd = (int)(blockIdx.x % kXcds), local = (int)(blockIdx.x / kXcds);
     const int tiles_here = (n_tiles + kXcds - 1) / kXcds;   // m-tiles per XCD (the last may not exist)
-    int slot, tile_local;
-    if (local < n_long * tiles_here) {
-        tile_local = local / n_long;
-        slot = local - tile_local * n_long;
-    } else {
-        const int rest = local - n_long * tiles_here, per = R - n_long;
-        tile_local = rest / per;
-        slot = n_long + rest - tile_local * per;
+    int slot = 0, tile_local = 0, rest = local;
+#pragma unroll
+    for (int g = 0; g < kMaxGroups; ++g) {
+        const int rows_g = groups.start[g + 1] - groups.start[g];
+        const int size_g = rows_g * tiles_here;
+        if (g < groups.n && rest >= 0 && rest < size_g) {
+            tile_local = rest / rows_g;
+            slot = groups.start[g] + rest - tile_local * rows_g;
+            rest = -1;
+        } else if (g < groups.n && rest >= 0) {
+            rest -= size_g;
+        }
     }
     const int tile = tile_local * kXcds + xcd;
     if (tile >= n_tiles) return;                      // whole workgroup leaves together
@@ -211,7 +225,7 @@ __global__ __launch_bounds__(256) void bsr_mfma_tile(const T* __restrict__ X, co
         const int row = pass * RPP + orow;
         const u32x4 v = *reinterpret_cast<const u32x4*>(ol + (size_t)row * OS + opiece * 16);
         const int i = i_base + wave * (MT * MM) + row;
-        if (i < m) *reinterpret_cast<u32x4*>(ybytes + (size_t)i * (size_t)n * sizeof(O) + opiece * 16) = v;
+        if (i < m) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(ybytes + (size_t)i * (size_t)n * sizeof(O) + opiece * 16));
     }
 }
 
@@ -228,7 +242,26 @@ bsr_status launch_tile_shape(const spmm_args& a, const tune_opts& tune)
             constexpr int D = decltype(d_tag)::value;
             constexpr int TM = 4 * MT * 32;
             const int n_tiles = (m + TM - 1) / TM;
-            const int n_long = tune.b > 0 ? (tune.b - 1 < R ? tune.b - 1 : R - 1) : W->long_rows;
+            // groups: the long rows, then runs of slots holding about `target` stored blocks each
+            // (a group's W: target * block bytes, chosen near 1.5 MB of the 4 MB L2)
+            slot_groups groups{};
+            {
+                const int n_long = W->long_rows;
+                const size_t block_bytes = (size_t)BS_R * BS_C * sizeof(T);
+                int64_t target = tune.b > 0 ? tune.b : (int64_t)((3u << 19) / block_bytes);
+                if (target < 1) target = 1;
+                int g = 0;
+                groups.start[0] = 0;
+                if (n_long > 0) groups.start[++g] = n_long;
+                int64_t acc_blocks = 0;
+                for (int s = n_long; s < R; ++s) {
+                    acc_blocks += W->slot_blocks[(size_t)s];
+                    if (acc_blocks >= target && g < kMaxGroups - 1 && s + 1 < R) { groups.start[++g] = s + 1; acc_blocks = 0; }
+                }
+                groups.start[++g] = R;
+                groups.n = g;
+                for (int q = g + 1; q <= kMaxGroups; ++q) groups.start[q] = R;
+            }
             const int64_t blocks = (int64_t)((n_tiles + kXcds - 1) / kXcds) * kXcds * R;
             if (blocks >= ((int64_t)1 << 31) || blocks * 256 >= ((int64_t)1 << 32)) return BSR_ERR_SHAPE;
             const size_t lds_stage = (size_t)(TM + BS_R) * (BS_C * sizeof(T) + 16);
@@ -242,7 +275,7 @@ bsr_status launch_tile_shape(const spmm_args& a, const tune_opts& tune)
             }
             hipLaunchKernelGGL((bsr_mfma_tile<T, O, BS_R, BS_C, MT, D>), dim3((unsigned)blocks), dim3(256), lds, a.stream,
                                (const T*)a.X, (const T*)W->data, W->indices, W->row_desc, (O*)a.Y, m, k, n, R, n_tiles,
-                               n_long);
+                               groups);
             return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
         };
         const int depth = tune.a > 0 ? tune.a : 2;
