@@ -33,12 +33,11 @@ size_t item_table_bytes(int64_t R)
 
 size_t plan_bytes(int64_t R, int64_t nnzb)
 {
-    // row order (R int32, padded to 256 B) + row descriptors (16 int32 per block-row) + spare room
-    // for per-block work lists; rounded up to 256 bytes
-    // ... + the k-split kernel's work-item table (up to 2*kMaxKsplitItems + 256 descriptors)
-    // (row order 4R + descriptors 64R + pair pointers 4R + pair entries: 16 bytes each, at most
-    // nnzb/2 + kStripeChunkPairs per block-row; each part padded to 256 B)
-    size_t b = (72 + 16 * (size_t)kStripeChunkPairs + 16) * (size_t)R + 8 * (size_t)nnzb + 2048 + item_table_bytes(R);
+    // row order (4R bytes) + row descriptors + pair pointers (4R) + pair entries (16 bytes each, at
+    // most nnzb/2 + kStripeChunkPairs per block-row), each part padded to 256 bytes, + the k-split
+    // kernel's work-item table (up to 2*kMaxKsplitItems + 256 descriptors)
+    const size_t per_row = 4 + 4 * (size_t)kRowDescWords + 4 + 16 * (size_t)kStripeChunkPairs + 16;
+    size_t b = per_row * (size_t)R + 8 * (size_t)nnzb + 2048 + item_table_bytes(R);
     return (b + 255) & ~(size_t)255;
 }
 

@@ -10,8 +10,8 @@
 
 #include "bsr_spmm.h"
 
-// Row descriptor (64 bytes): {block-row, first stored block, block count, m-tile, 12 block-columns}.
-constexpr int kRowDescWords = 16;
+// Row descriptor (128 bytes): {block-row, first stored block, block count, m-tile, 28 block-columns}.
+constexpr int kRowDescWords = 32;
 constexpr int kRowDescColsAt = 4;                 // word index of the first inline block-column
 constexpr int kRowDescCols = kRowDescWords - kRowDescColsAt;
 constexpr int kMaxKsplitItems = 4096;             // the k-split kernel is used below this many (block-row, m-tile) items

@@ -7,11 +7,64 @@
 // which keeps the result deterministic.  This is the paper's concurrent reduction (Section 4.4:
 // several threads share one output's reduction, partial results aggregated at the end) moved from
 // single output elements to MFMA tiles.
+//
+// Operands reach the matrix cores through LDS.  An MFMA operand wants lane l to hold a run of ROW
+// l mod MM, so neighbouring lanes would read addresses a whole row apart, and the memory pipeline
+// serves such 16-byte pieces one per cycle (measured: 16 B/clk per CU against 58 B/clk when
+// neighbouring lanes read neighbouring pieces).  So a wavefront reads its W block and its X tile
+// with lane l taking piece l of the contiguous data, writes them to its own LDS area (rows padded
+// by 16 bytes) and reads them back in operand order.  The area belongs to one wavefront, whose LDS
+// operations complete in order: no barrier.  Loads are buffer loads: a block the wavefront does
+// not have and rows of X past m read as zeros without touching memory, which keeps the loads of a
+// round unconditional (all in flight at once, two blocks per wavefront).
 #include "bsr_mfma_common.h"
 
 using namespace bsr_dev;
 
 namespace {
+
+constexpr unsigned kDead = 0x80000000u;               // byte offset no buffer reaches: reads as zero
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// Buffer resource over [base, base + bytes): raw 32-bit data, no swizzle.
+__device__ __forceinline__ i32x4 make_rsrc(const void* base, int bytes)
+{
+    const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+    i32x4 r;
+    r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
+    r.y = __builtin_amdgcn_readfirstlane((int)(unsigned)(a >> 32) & 0xFFFF);
+    r.z = __builtin_amdgcn_readfirstlane(bytes);
+    r.w = 0x00020000;
+    return r;
+}
+
+// 16-byte buffer load the compiler neither moves nor waits for: the caller places s_waitcnt itself
+// (the compiler would otherwise sink the loads of a wavefront's second block behind the
+// arithmetic of its first).
+__device__ __forceinline__ void load_b128(u32x4& dst, const i32x4& rsrc, unsigned offset)
+{
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(dst) : "v"(offset), "s"(rsrc));
+}
+template <int N> __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N)); }
+__device__ __forceinline__ void arrived(u32x4& v) { asm volatile("" : "+v"(v)); }   // use v only below this point
+
+template <typename T, int BS_R, int BS_C>
+struct ksplit_geom {
+    static constexpr int MM = BS_R >= 32 ? 32 : 16;
+    static constexpr int S = (int)sizeof(T);
+    static constexpr int RBS = BS_C * S;               // bytes of a block's row (and of an X tile's row)
+    static constexpr int P = RBS + 16;                 // padded LDS row
+    static constexpr int BLK = BS_R * RBS;             // bytes of a stored block
+    static constexpr int NLW = (BLK + 1023) / 1024;    // 1 KiB load instructions per block
+    static constexpr int LPR = RBS / 16;               // X tile: lanes per row
+    static constexpr int RPI = 64 / LPR;               //         rows per load instruction
+    static constexpr int NLX = (MM + RPI - 1) / RPI;   //         load instructions
+    static constexpr int LD = BS_R + 4;                // padded row of the fp32 partial-sum tile
+    static constexpr int STAGE = (BS_R + MM) * P;      // W block + X tile
+    static constexpr int PART = MM * LD * 4;           // partial-sum tile (reuses the staging area)
+    static constexpr int REGION = ((STAGE > PART ? STAGE : PART) + 15) & ~15;   // LDS bytes per wavefront
+};
 
 template <typename T, typename O, int BS_R, int BS_C>
 __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, const T* __restrict__ data,
@@ -19,32 +72,34 @@ __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, 
                                                        const int32_t* __restrict__ row_desc, O* __restrict__ Y,
                                                        int m, int k, int n, int R, int per, int items)
 {
-    constexpr int MM = BS_R >= 32 ? 32 : 16;
+    typedef ksplit_geom<T, BS_R, BS_C> geo;
+    constexpr int MM = geo::MM, S = geo::S, RBS = geo::RBS, P = geo::P, BLK = geo::BLK;
+    constexpr int NLW = geo::NLW, LPR = geo::LPR, RPI = geo::RPI, NLX = geo::NLX, LD = geo::LD;
     constexpr int NA = BS_R / MM;
     constexpr int G = 64 / MM;
     constexpr int CH = BS_C / G;
     constexpr int NE = MM == 32 ? 16 : 4;             // accumulator values per lane and tile
-    constexpr int LD = BS_R + 4;                      // padded row of the LDS partial-sum tile
     typedef typename AccT<MM>::type acc_t;
-    extern __shared__ float red[];                    // [NW][MM][LD]
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];   // [wavefronts][REGION]
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nw_max = blockDim.x >> 6;
     const int li = lane % MM, h = lane / MM;
-    // one read of the workgroup's descriptor: block-row, first stored block, count, m-tile, first
-    // block-columns.  With a work-item table (items != 0) workgroup b takes entry b -- the table is
-    // laid out so that the workgroups sharing a CU carry about equal work -- and an entry with
-    // block-row -1 is a filler; without one, workgroup b takes slot b mod R of m-tile b div R.
+    // One read of the workgroup's descriptor, a word per lane: block-row, first stored block, count,
+    // m-tile, first block-columns.  With a work-item table (items != 0) workgroup b takes entry b --
+    // the table is laid out so that the workgroups sharing a CU carry about equal work -- and an
+    // entry with block-row -1 is a filler; without one, workgroup b takes slot b mod R of m-tile b div R.
     const int32_t* __restrict__ desc =
         row_desc + (size_t)(items ? blockIdx.x : blockIdx.x % (unsigned)R) * kRowDescWords;
-    const int r = desc[0];
+    const int dword = lane < kRowDescWords ? desc[lane] : 0;
+    const int r = __builtin_amdgcn_readlane(dword, 0);
     if (r < 0) return;                                // whole workgroup leaves together
-    const int i_base = (items ? desc[3] : (int)(blockIdx.x / (unsigned)R)) * MM;
-    const int p0 = desc[1], p1 = p0 + desc[2];
+    const int p0 = __builtin_amdgcn_readlane(dword, 1), cnt = __builtin_amdgcn_readlane(dword, 2);
+    const int i_base = (items ? __builtin_amdgcn_readlane(dword, 3) : (int)(blockIdx.x / (unsigned)R)) * MM;
     // wavefronts that take part: about `per` stored blocks each, at most all of the workgroup's;
-    // the others go straight to the barrier, so short block-rows cost no loads in idle wavefronts
-    const int nw = max(1, min(nw_max, (p1 - p0 + per - 1) / per));
+    // the others go straight to the barrier
+    const int nw = max(1, min(nw_max, (cnt + per - 1) / per));
 
     acc_t acc[NA];
 #pragma unroll
@@ -52,38 +107,75 @@ __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, 
 #pragma unroll
         for (int e = 0; e < NE; ++e) acc[u][e] = 0.f;
 
-    const T* xbase = X + (size_t)min(i_base + li, m - 1) * (size_t)k + h * CH;
-    const T* wbase = data + (size_t)li * BS_C + h * CH;
+    unsigned char* wl = lds + (size_t)wave * geo::REGION;      // this wavefront's W block, [BS_R][P]
+    unsigned char* xl = wl + BS_R * P;                         // and X tile, [MM][P]
 
-    Frag<T, CH> wf[2][NA], xf[2];
-    auto fetch = [&](int buf, int p) {
-        const int j = p - p0;
-        const int c = j < kRowDescCols ? desc[kRowDescColsAt + j] : indices[p];
-        const T* wp = wbase + (size_t)p * (BS_R * BS_C);
+    if (wave < nw) {
+        // W of this block-row and the X rows of this m-tile as buffers: offsets past their ends read zero
+        const i32x4 wrsrc = make_rsrc(data + (size_t)p0 * (BS_R * BS_C), cnt * BLK);
+        const i32x4 xrsrc = make_rsrc(X + (size_t)i_base * (size_t)k, min(MM, m - i_base) * k * S);
+        // lane's pieces: W piece t is bytes t*1024 + lane*16 of the block; X piece t is 16 bytes of
+        // row t*RPI + lane/LPR of the tile
+        unsigned w_g[NLW], w_l[NLW], x_g[NLX], x_l[NLX];
 #pragma unroll
-        for (int u = 0; u < NA; ++u) wf[buf][u].load(wp + u * (MM * BS_C));
-        xf[buf].load(xbase + (size_t)c * BS_C);
-    };
-    auto compute = [&](int buf) {
+        for (int t = 0; t < NLW; ++t) {
+            const unsigned b = (unsigned)(t * 1024 + lane * 16);
+            w_g[t] = b < (unsigned)BLK ? b : kDead;
+            w_l[t] = (b / RBS) * P + (b % RBS);
+        }
 #pragma unroll
-        for (int u = 0; u < NA; ++u) mfma_frag<T, MM, CH>(acc[u], wf[buf][u], xf[buf]);
-    };
+        for (int t = 0; t < NLX; ++t) {
+            const unsigned row = (unsigned)(t * RPI + lane / LPR), piece = (unsigned)(lane % LPR);
+            x_g[t] = row < (unsigned)MM ? row * (unsigned)(k * S) + piece * 16 : kDead;
+            x_l[t] = row * P + piece * 16;
+        }
+        const unsigned char* wop = wl + li * P + h * (CH * S);       // lane's operand runs
+        const unsigned char* xop = xl + li * P + h * (CH * S);
 
-    int p = wave < nw ? p0 + wave : p1;
-    if (p < p1) fetch(0, p);
-    while (p < p1) {
-        if (p + nw < p1) fetch(1, p + nw);
-        compute(0);
-        p += nw;
-        if (p >= p1) break;
-        if (p + nw < p1) fetch(0, p + nw);
-        compute(1);
-        p += nw;
+        // a round: every wavefront takes up to two blocks, all loads of both issued before any is used
+        for (int j0 = wave; j0 < cnt; j0 += 2 * nw) {
+            u32x4 gw[2][NLW], gx[2][NLX];
+            bool have[2];
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const int j = j0 + s * nw;
+                have[s] = j < cnt;                              // uniform
+                int c = 0;
+                if (have[s]) c = j < kRowDescCols ? __builtin_amdgcn_readlane(dword, kRowDescColsAt + j) : indices[p0 + j];
+                // a dead piece stays dead: kDead plus an offset inside the buffer is still past its end
+#pragma unroll
+                for (int t = 0; t < NLW; ++t) load_b128(gw[s][t], wrsrc, have[s] ? w_g[t] + (unsigned)j * BLK : kDead);
+#pragma unroll
+                for (int t = 0; t < NLX; ++t) load_b128(gx[s][t], xrsrc, have[s] ? x_g[t] + (unsigned)c * RBS : kDead);
+            }
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                if (s == 0) wait_loads<NLW + NLX>(); else wait_loads<0>();   // loads return in issue order
+#pragma unroll
+                for (int t = 0; t < NLW; ++t) arrived(gw[s][t]);
+#pragma unroll
+                for (int t = 0; t < NLX; ++t) arrived(gx[s][t]);
+                if (!have[s]) continue;                         // uniform
+#pragma unroll
+                for (int t = 0; t < NLW; ++t)
+                    if (BLK % 1024 == 0 || t * 1024 + lane * 16 < BLK) *reinterpret_cast<u32x4*>(wl + w_l[t]) = gw[s][t];
+#pragma unroll
+                for (int t = 0; t < NLX; ++t)
+                    if (MM % RPI == 0 || t * RPI + lane / LPR < MM) *reinterpret_cast<u32x4*>(xl + x_l[t]) = gx[s][t];
+                Frag<T, CH> wf[NA], xf;
+#pragma unroll
+                for (int u = 0; u < NA; ++u) wf[u].load(reinterpret_cast<const T*>(wop + u * (MM * P)));
+                xf.load(reinterpret_cast<const T*>(xop));
+#pragma unroll
+                for (int u = 0; u < NA; ++u) mfma_frag<T, MM, CH>(acc[u], wf[u], xf);
+            }
+        }
     }
-    // partial sums of the wavefronts that had at least one block -> LDS
-    const int used = min(nw, p1 - p0);
+    // partial sums of the wavefronts that had at least one block -> LDS (over the wavefront's own
+    // staging area, whose contents it has already consumed)
+    const int used = min(nw, cnt);
     if (wave < used) {
-        float* mine = red + ((size_t)wave * MM + li) * LD;
+        float* mine = reinterpret_cast<float*>(wl) + (size_t)li * LD;
 #pragma unroll
         for (int u = 0; u < NA; ++u) {
             if constexpr (MM == 32) {
@@ -105,7 +197,8 @@ __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, 
     for (int t = threadIdx.x; t < MM * QUADS; t += blockDim.x) {
         const int i = t / QUADS, q = t - i * QUADS;
         f32x4 s = {0.f, 0.f, 0.f, 0.f};
-        for (int w = 0; w < used; ++w) s += *reinterpret_cast<const f32x4*>(red + ((size_t)w * MM + i) * LD + 4 * q);
+        for (int w = 0; w < used; ++w)
+            s += *reinterpret_cast<const f32x4*>(lds + (size_t)w * geo::REGION + ((size_t)i * LD + 4 * q) * 4);
         if (i_base + i < m)
             store4<O>(Y + (size_t)(i_base + i) * (size_t)n + (size_t)r * BS_R + 4 * q, s.x, s.y, s.z, s.w);
     }
@@ -114,15 +207,20 @@ __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, 
 template <typename T, typename O, int BS_R, int BS_C>
 bsr_status launch_ksplit_shape(const spmm_args& a, const tune_opts& tune)
 {
+    typedef ksplit_geom<T, BS_R, BS_C> geo;
     const bsr_matrix* W = a.W;
     const int m = (int)a.m, n = (int)W->n, k = (int)W->k, R = W->R;
-    constexpr int MM = BS_R >= 32 ? 32 : 16;
-    // wavefronts per workgroup: about one stored block each for the average block-row, 1..8
-    // blocks per wavefront `per`, and as many wavefronts as the longest block-row then needs (1..8)
+    constexpr int MM = geo::MM;
+    // 32-bit byte offsets inside a block-row's blocks and inside an m-tile's rows of X
+    if ((int64_t)W->max_row_blocks * geo::BLK >= ((int64_t)1 << 31) || (int64_t)MM * k * geo::S >= ((int64_t)1 << 31))
+        return BSR_ERR_UNSUPPORTED;
+    // wavefronts per workgroup: about `per` stored blocks each for the longest block-row, 1..8, and
+    // no more than LDS has room for
     int per = tune.a > 0 ? tune.a : 2;
     int nw = (W->max_row_blocks + per - 1) / per;
     nw = nw < 1 ? 1 : (nw > 8 ? 8 : nw);
     if (tune.nw >= 1 && tune.nw <= 8) nw = tune.nw;
+    nw = std::min(nw, 160 * 1024 / geo::REGION);
     const int64_t tiles = (m + MM - 1) / MM;
     int64_t blocks = tiles * R;
     if (blocks >= ((int64_t)1 << 31) || blocks * 64 * nw >= ((int64_t)1 << 32)) return BSR_ERR_SHAPE;
@@ -133,7 +231,11 @@ bsr_status launch_ksplit_shape(const spmm_args& a, const tune_opts& tune)
         const int grid = ksplit_items(W, (int)tiles, a.stream);
         if (grid > 0) { table = W->item_desc; items = 1; blocks = grid; }
     }
-    const size_t lds = (size_t)nw * MM * (BS_R + 4) * sizeof(float);
+    const size_t lds = (size_t)nw * geo::REGION;
+    static const hipError_t attr =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&bsr_mfma_ksplit<T, O, BS_R, BS_C>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (attr != hipSuccess) return BSR_ERR_HIP;
     hipLaunchKernelGGL((bsr_mfma_ksplit<T, O, BS_R, BS_C>), dim3((unsigned)blocks), dim3(64 * nw), lds, a.stream,
                        (const T*)a.X, (const T*)W->data, W->indices, table, (O*)a.Y, m, k, n, R, per, items);
     return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
