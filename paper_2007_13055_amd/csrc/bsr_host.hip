@@ -122,6 +122,7 @@ int ksplit_items(const bsr_matrix* W, int tiles, hipStream_t stream)
         return 0;
     W->item_tiles = tiles;
     W->item_grid = (int)grid;
+    W->item_cus = n_cu;
     return W->item_grid;
 }
 

@@ -45,6 +45,7 @@ struct bsr_matrix {
     mutable std::mutex item_mu;              // guards the cache below
     mutable int item_tiles = -1;             // m-tiles the cached table was built for (-1: none)
     mutable int item_grid = 0;               // workgroups of the cached table
+    mutable int item_cus = 0;                // CUs the cached table was laid out for (entry b runs on CU b mod item_cus)
     mutable std::vector<int32_t> item_host;  // host copy (kept alive for the asynchronous upload)
     int32_t max_row_blocks = 0;              // longest block-row
     int32_t long_rows = 0;                   // leading slots whose block count is > 4x the mean and > 8 ("long" bin)

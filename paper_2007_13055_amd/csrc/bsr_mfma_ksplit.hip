@@ -15,8 +15,8 @@
 // with lane l taking piece l of the contiguous data, writes them to its own LDS area (rows padded
 // by 16 bytes) and reads them back in operand order.  The area belongs to one wavefront, whose LDS
 // operations complete in order: no barrier.  Loads are buffer loads: a block the wavefront does
-// not have and rows of X past m read as zeros without touching memory, which keeps the loads of a
-// round unconditional (all in flight at once, two blocks per wavefront).
+// not have and rows of X past m read as zeros without touching memory, which keeps a wavefront's
+// loads unconditional and their number in flight fixed (two blocks ahead).
 #include "bsr_mfma_common.h"
 
 using namespace bsr_dev;
@@ -49,9 +49,9 @@ __device__ __forceinline__ void load_b128(u32x4& dst, const i32x4& rsrc, unsigne
 template <int N> __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N)); }
 __device__ __forceinline__ void arrived(u32x4& v) { asm volatile("" : "+v"(v)); }   // use v only below this point
 
-template <typename T, int BS_R, int BS_C>
+template <typename T, int BS_R, int BS_C, int MM_>
 struct ksplit_geom {
-    static constexpr int MM = BS_R >= 32 ? 32 : 16;
+    static constexpr int MM = MM_;                     // rows of X per workgroup = MFMA tile edge
     static constexpr int S = (int)sizeof(T);
     static constexpr int RBS = BS_C * S;               // bytes of a block's row (and of an X tile's row)
     static constexpr int P = RBS + 16;                 // padded LDS row
@@ -66,13 +66,13 @@ struct ksplit_geom {
     static constexpr int REGION = ((STAGE > PART ? STAGE : PART) + 15) & ~15;   // LDS bytes per wavefront
 };
 
-template <typename T, typename O, int BS_R, int BS_C>
+template <typename T, typename O, int BS_R, int BS_C, int MM_>
 __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, const T* __restrict__ data,
                                                        const int32_t* __restrict__ indices,
                                                        const int32_t* __restrict__ row_desc, O* __restrict__ Y,
                                                        int m, int k, int n, int R, int per, int items)
 {
-    typedef ksplit_geom<T, BS_R, BS_C> geo;
+    typedef ksplit_geom<T, BS_R, BS_C, MM_> geo;
     constexpr int MM = geo::MM, S = geo::S, RBS = geo::RBS, P = geo::P, BLK = geo::BLK;
     constexpr int NLW = geo::NLW, LPR = geo::LPR, RPI = geo::RPI, NLX = geo::NLX, LD = geo::LD;
     constexpr int NA = BS_R / MM;
@@ -83,11 +83,12 @@ __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];   // [wavefronts][REGION]
 
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int hw_wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nw_max = blockDim.x >> 6;
     const int li = lane % MM, h = lane / MM;
     // One read of the workgroup's descriptor, a word per lane: block-row, first stored block, count,
-    // m-tile, first block-columns.  With a work-item table (items != 0) workgroup b takes entry b --
+    // m-tile, first block-columns.  With a work-item table (items = the number of CUs it was laid out
+    // for, else 0) workgroup b takes entry b --
     // the table is laid out so that the workgroups sharing a CU carry about equal work -- and an
     // entry with block-row -1 is a filler; without one, workgroup b takes slot b mod R of m-tile b div R.
     const int32_t* __restrict__ desc =
@@ -100,6 +101,11 @@ __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, 
     // wavefronts that take part: about `per` stored blocks each, at most all of the workgroup's;
     // the others go straight to the barrier
     const int nw = max(1, min(nw_max, (cnt + per - 1) / per));
+    // Wavefront w of a workgroup runs on SIMD w mod 4 and the low-numbered wavefronts get a block-row's
+    // odd blocks.  The workgroups stacked on one CU (table entries b, b + #CUs, ...) therefore number
+    // their wavefronts from different starts: `wave` is the number used for sharing out blocks and
+    // for the order of the final sum; wavefronts nw and up take no part.
+    const int wave = hw_wave < nw ? (hw_wave + (items ? (int)(blockIdx.x / (unsigned)items) : 0)) % nw : hw_wave;
 
     acc_t acc[NA];
 #pragma unroll
@@ -110,7 +116,7 @@ __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, 
     unsigned char* wl = lds + (size_t)wave * geo::REGION;      // this wavefront's W block, [BS_R][P]
     unsigned char* xl = wl + BS_R * P;                         // and X tile, [MM][P]
 
-    if (wave < nw) {
+    if (wave < nw && wave < cnt) {                     // this wavefront has at least one block
         // W of this block-row and the X rows of this m-tile as buffers: offsets past their ends read zero
         const i32x4 wrsrc = make_rsrc(data + (size_t)p0 * (BS_R * BS_C), cnt * BLK);
         const i32x4 xrsrc = make_rsrc(X + (size_t)i_base * (size_t)k, min(MM, m - i_base) * k * S);
@@ -132,44 +138,51 @@ __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, 
         const unsigned char* wop = wl + li * P + h * (CH * S);       // lane's operand runs
         const unsigned char* xop = xl + li * P + h * (CH * S);
 
-        // a round: every wavefront takes up to two blocks, all loads of both issued before any is used
-        for (int j0 = wave; j0 < cnt; j0 += 2 * nw) {
-            u32x4 gw[2][NLW], gx[2][NLX];
-            bool have[2];
+        // The wavefront's blocks are j = wave, wave + nw, ...; two register sets alternate, so the
+        // loads of the next two blocks are in flight while one is multiplied.
+        u32x4 gw[2][NLW], gx[2][NLX];
+        auto issue = [&](int s, int j) {
+            const int c = j < kRowDescCols ? __builtin_amdgcn_readlane(dword, kRowDescColsAt + j) : indices[p0 + j];
 #pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                const int j = j0 + s * nw;
-                have[s] = j < cnt;                              // uniform
-                int c = 0;
-                if (have[s]) c = j < kRowDescCols ? __builtin_amdgcn_readlane(dword, kRowDescColsAt + j) : indices[p0 + j];
-                // a dead piece stays dead: kDead plus an offset inside the buffer is still past its end
+            for (int t = 0; t < NLW; ++t) load_b128(gw[s][t], wrsrc, w_g[t] + (unsigned)j * BLK);
 #pragma unroll
-                for (int t = 0; t < NLW; ++t) load_b128(gw[s][t], wrsrc, have[s] ? w_g[t] + (unsigned)j * BLK : kDead);
+            for (int t = 0; t < NLX; ++t) load_b128(gx[s][t], xrsrc, x_g[t] + (unsigned)c * RBS);
+        };
+        // `behind`: another block's loads were issued after this one's (loads return in issue order)
+        auto consume = [&](int s, bool behind) {
+            if (behind) wait_loads<NLW + NLX>(); else wait_loads<0>();   // uniform
 #pragma unroll
-                for (int t = 0; t < NLX; ++t) load_b128(gx[s][t], xrsrc, have[s] ? x_g[t] + (unsigned)c * RBS : kDead);
-            }
+            for (int t = 0; t < NLW; ++t) arrived(gw[s][t]);
 #pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                if (s == 0) wait_loads<NLW + NLX>(); else wait_loads<0>();   // loads return in issue order
+            for (int t = 0; t < NLX; ++t) arrived(gx[s][t]);
 #pragma unroll
-                for (int t = 0; t < NLW; ++t) arrived(gw[s][t]);
+            for (int t = 0; t < NLW; ++t)
+                if (BLK % 1024 == 0 || t * 1024 + lane * 16 < BLK) *reinterpret_cast<u32x4*>(wl + w_l[t]) = gw[s][t];
 #pragma unroll
-                for (int t = 0; t < NLX; ++t) arrived(gx[s][t]);
-                if (!have[s]) continue;                         // uniform
+            for (int t = 0; t < NLX; ++t)
+                if (MM % RPI == 0 || t * RPI + lane / LPR < MM) *reinterpret_cast<u32x4*>(xl + x_l[t]) = gx[s][t];
+            Frag<T, CH> wf[NA], xf;
 #pragma unroll
-                for (int t = 0; t < NLW; ++t)
-                    if (BLK % 1024 == 0 || t * 1024 + lane * 16 < BLK) *reinterpret_cast<u32x4*>(wl + w_l[t]) = gw[s][t];
+            for (int u = 0; u < NA; ++u) wf[u].load(reinterpret_cast<const T*>(wop + u * (MM * P)));
+            xf.load(reinterpret_cast<const T*>(xop));
 #pragma unroll
-                for (int t = 0; t < NLX; ++t)
-                    if (MM % RPI == 0 || t * RPI + lane / LPR < MM) *reinterpret_cast<u32x4*>(xl + x_l[t]) = gx[s][t];
-                Frag<T, CH> wf[NA], xf;
-#pragma unroll
-                for (int u = 0; u < NA; ++u) wf[u].load(reinterpret_cast<const T*>(wop + u * (MM * P)));
-                xf.load(reinterpret_cast<const T*>(xop));
-#pragma unroll
-                for (int u = 0; u < NA; ++u) mfma_frag<T, MM, CH>(acc[u], wf[u], xf);
+            for (int u = 0; u < NA; ++u) mfma_frag<T, MM, CH>(acc[u], wf[u], xf);
+        };
+        // every load issued below is waited for before the wavefront ends: none is left in flight
+        issue(0, wave);
+        bool odd = wave + nw < cnt;                             // set 1 holds a block (all uniform)
+        if (odd) issue(1, wave + nw);
+        for (int j = wave; j < cnt; j += 2 * nw) {
+            consume(0, odd);
+            const bool next = j + 2 * nw < cnt;
+            if (next) issue(0, j + 2 * nw);
+            if (odd) {
+                consume(1, next);
+                odd = j + 3 * nw < cnt;
+                if (odd) issue(1, j + 3 * nw);
             }
         }
+        wait_loads<0>();
     }
     // partial sums of the wavefronts that had at least one block -> LDS (over the wavefront's own
     // staging area, whose contents it has already consumed)
@@ -204,41 +217,60 @@ __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, 
     }
 }
 
-template <typename T, typename O, int BS_R, int BS_C>
-bsr_status launch_ksplit_shape(const spmm_args& a, const tune_opts& tune)
+template <typename T, typename O, int BS_R, int BS_C, int MM>
+bsr_status launch_ksplit_tile(const spmm_args& a, const tune_opts& tune)
 {
-    typedef ksplit_geom<T, BS_R, BS_C> geo;
+    typedef ksplit_geom<T, BS_R, BS_C, MM> geo;
     const bsr_matrix* W = a.W;
     const int m = (int)a.m, n = (int)W->n, k = (int)W->k, R = W->R;
-    constexpr int MM = geo::MM;
     // 32-bit byte offsets inside a block-row's blocks and inside an m-tile's rows of X
     if ((int64_t)W->max_row_blocks * geo::BLK >= ((int64_t)1 << 31) || (int64_t)MM * k * geo::S >= ((int64_t)1 << 31))
         return BSR_ERR_UNSUPPORTED;
-    // wavefronts per workgroup: about `per` stored blocks each for the longest block-row, 1..8, and
-    // no more than LDS has room for
-    int per = tune.a > 0 ? tune.a : 2;
-    int nw = (W->max_row_blocks + per - 1) / per;
-    nw = nw < 1 ? 1 : (nw > 8 ? 8 : nw);
-    if (tune.nw >= 1 && tune.nw <= 8) nw = tune.nw;
-    nw = std::min(nw, 160 * 1024 / geo::REGION);
+    // wavefronts per workgroup: about `per` stored blocks each for the longest block-row; at most 8
+    // when every workgroup has a CU to itself, at most 4 otherwise (starting wavefronts costs time
+    // too: about 11 cycles each per XCD), and no more than LDS has room for
     const int64_t tiles = (m + MM - 1) / MM;
     int64_t blocks = tiles * R;
+    int per = tune.a > 0 ? tune.a : 2;
+    int nw = (W->max_row_blocks + per - 1) / per;
+    const int nw_cap = blocks > 256 ? 4 : 8;
+    nw = nw < 1 ? 1 : (nw > nw_cap ? nw_cap : nw);
+    if (tune.nw >= 1 && tune.nw <= 8) nw = tune.nw;
+    nw = std::min(nw, 160 * 1024 / geo::REGION);
     if (blocks >= ((int64_t)1 << 31) || blocks * 64 * nw >= ((int64_t)1 << 32)) return BSR_ERR_SHAPE;
     // CU-balanced work-item table when there are more items than CUs (else every item has a CU to itself)
     const int32_t* table = W->row_desc;
     int items = 0;
     if (tune.b != 1 && blocks > 256 && blocks <= kMaxKsplitItems) {
         const int grid = ksplit_items(W, (int)tiles, a.stream);
-        if (grid > 0) { table = W->item_desc; items = 1; blocks = grid; }
+        if (grid > 0) { table = W->item_desc; items = W->item_cus; blocks = grid; }
     }
     const size_t lds = (size_t)nw * geo::REGION;
     static const hipError_t attr =
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&bsr_mfma_ksplit<T, O, BS_R, BS_C>),
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&bsr_mfma_ksplit<T, O, BS_R, BS_C, MM>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (attr != hipSuccess) return BSR_ERR_HIP;
-    hipLaunchKernelGGL((bsr_mfma_ksplit<T, O, BS_R, BS_C>), dim3((unsigned)blocks), dim3(64 * nw), lds, a.stream,
+    hipLaunchKernelGGL((bsr_mfma_ksplit<T, O, BS_R, BS_C, MM>), dim3((unsigned)blocks), dim3(64 * nw), lds, a.stream,
                        (const T*)a.X, (const T*)W->data, W->indices, table, (O*)a.Y, m, k, n, R, per, items);
     return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
+}
+
+// Rows of X per workgroup: 32 (the larger MFMA tile: every W block is fetched half as often) when
+// that still leaves at least three workgroups per CU to even out block-rows of different length,
+// else 16.  16-bit blocks narrower than 32 columns stay at 32 rows where they can: their 16-row
+// MFMA would run at half rate.
+template <typename T, typename O, int BS_R, int BS_C>
+bsr_status launch_ksplit_shape(const spmm_args& a, const tune_opts& tune)
+{
+    if constexpr (BS_R >= 32) {
+        const int64_t items32 = (a.m + 31) / 32 * a.W->R;
+        const bool slow16 = sizeof(T) == 2 && BS_C < 32;
+        bool tall = items32 >= 768 || slow16;
+        if (tune.mt == 1) tall = false;
+        if (tune.mt == 2) tall = true;
+        if (tall) return launch_ksplit_tile<T, O, BS_R, BS_C, 32>(a, tune);
+    }
+    return launch_ksplit_tile<T, O, BS_R, BS_C, 16>(a, tune);
 }
 
 }  // namespace
