@@ -18,13 +18,14 @@ using namespace bsr_dev;
 
 namespace {
 
-// XT[c][i] = X[i][c]; tiles of 32 rows x 64 columns of X through LDS, 16 bytes per lane on both sides.
-__global__ __launch_bounds__(256) void transpose_f32(const float* __restrict__ X, float* __restrict__ XT, int m, int k)
+// XT[c][i] = X[i][c], rows of XT mp floats apart (m rounded up to a multiple of 4, so every row starts
+// 16-byte aligned); tiles of 32 rows x 64 columns of X through LDS, 16 bytes per lane on both sides.
+__global__ __launch_bounds__(256) void transpose_f32(const float* __restrict__ X, float* __restrict__ XT, int m, int k, int mp)
 {
     constexpr int TI = 32, TC = 64;
     __shared__ float tile[TI][TC + 1];
     const int c0 = blockIdx.x * TC, i0 = blockIdx.y * TI;
-    const bool full = c0 + TC <= k && i0 + TI <= m && (k & 3) == 0 && (m & 3) == 0;
+    const bool full = c0 + TC <= k && i0 + TI <= m && (k & 3) == 0;
     if (full) {
         {   // read: 16 lanes cover one row's 64 columns
             const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
@@ -42,7 +43,7 @@ __global__ __launch_bounds__(256) void transpose_f32(const float* __restrict__ X
             for (int j = 0; j < TC / 32; ++j) {
                 const int c = ty + 32 * j;
                 const f32x4 v = {tile[4 * tx][c], tile[4 * tx + 1][c], tile[4 * tx + 2][c], tile[4 * tx + 3][c]};
-                *reinterpret_cast<f32x4*>(XT + (size_t)(c0 + c) * m + i0 + 4 * tx) = v;
+                *reinterpret_cast<f32x4*>(XT + (size_t)(c0 + c) * mp + i0 + 4 * tx) = v;
             }
         }
     } else {                                          // ragged edge tile: element by element
@@ -53,7 +54,7 @@ __global__ __launch_bounds__(256) void transpose_f32(const float* __restrict__ X
         __syncthreads();
         for (int e = threadIdx.x; e < TI * TC; e += 256) {
             const int c = e / TI, i = e % TI;
-            if (c0 + c < k && i0 + i < m) XT[(size_t)(c0 + c) * m + i0 + i] = tile[i][c];
+            if (c0 + c < k && i0 + i < m) XT[(size_t)(c0 + c) * mp + i0 + i] = tile[i][c];
         }
     }
 }
@@ -63,9 +64,13 @@ __global__ __launch_bounds__(256) void transpose_f32(const float* __restrict__ X
 // 4.4: several threads share one output's reduction and the partial results are added at the end);
 // each keeps a 64 x 16 partial result, and the partial results are summed through LDS in fixed
 // order.  Per MFMA 16x16x4:
-//   A operand (rows of the result = rows of X): lane l supplies XT[col(p + l/16)][i0 + s*16 + l%16]
+//   A operand (rows of the result = rows of X): lane l supplies XT[col(p + l/16)][i0 + 4*(l%16) + s]
+//     for the s-th of the wavefront's 4 MFMAs -- the 16 rows of MFMA s are rows s, 4+s, 8+s, ... of
+//     the 64-row tile, so that ONE 16-byte load per lane (4 consecutive entries of an XT row) feeds
+//     all four; neighbouring lanes read neighbouring 16-byte pieces, which the memory pipeline
+//     serves four times faster than four 4-byte reads 64 bytes apart
 //   B operand (columns = the 16 outputs of the block-row): lane l supplies block_data[p + l/16][l%16]
-//   result: lane l holds rows 4*(l/16) + j (j = 0..3), column l%16
+//   result of MFMA s: lane l holds tile rows 16*(l/16) + 4*j + s (j = 0..3), column l%16
 // A wavefront loads the block-columns and the blocks of U groups of 4 blocks, then issues all
 // 4*U gathers from XT before the first MFMA, so one memory latency covers up to 4*U blocks.
 template <int U>
@@ -84,7 +89,7 @@ __global__ __launch_bounds__(256) void bsr_thin16_f32(const float* __restrict__ 
     const int32_t* __restrict__ desc = row_desc + (size_t)slot * kRowDescWords;
     const int r = desc[0];
     const int p0 = desc[1], nb = desc[2];
-    const unsigned row_bytes = (unsigned)m * 4u;      // one row of XT
+    const unsigned row_bytes = (unsigned)((m + 3) & ~3) * 4u;      // one row of XT (padded to 16 bytes)
     const int share = ((nb + 3) / 4 + 3) / 4 * 4;     // blocks per wavefront, a multiple of 4
     const int qb = p0 + min(wave * share, nb), qe = p0 + min((wave + 1) * share, nb);
 
@@ -95,7 +100,7 @@ __global__ __launch_bounds__(256) void bsr_thin16_f32(const float* __restrict__ 
     // Addressing is kept to "uniform base + per-lane 32-bit byte offset + immediate" so that a load
     // costs at most one vector ALU instruction:
     //   blocks / block-columns of group u: base(pb) + lane part + u*256 (resp. u*16) bytes
-    //   gather for tile s of group u:      XT + (col*m + i0 + lo)*4 + s*64 bytes
+    //   gather of group u:                 XT + (col*mp + i0 + 4*lo)*4 bytes, mp = m rounded up to 4
     // The gather may read up to 63 floats past the m valid entries of an XT row (rows of X past m in
     // the last tile): that lands in the next XT row, or in the scratch's tail padding for the last
     // one; those rows of the result are never stored.
@@ -103,7 +108,7 @@ __global__ __launch_bounds__(256) void bsr_thin16_f32(const float* __restrict__ 
     const unsigned char* w_bytes = reinterpret_cast<const unsigned char*>(data);
     const unsigned char* i_bytes = reinterpret_cast<const unsigned char*>(indices);
     const unsigned lane_w = (unsigned)(pp * 16 + lo) * 4u, lane_i = (unsigned)pp * 4u;
-    const unsigned lane_x = (unsigned)(i0 + lo) * 4u;
+    const unsigned lane_x = (unsigned)(i0 + 4 * lo) * 4u;
 
     for (int pb = qb; pb < qe; pb += 4 * U) {
         float wv[U];
@@ -129,13 +134,10 @@ __global__ __launch_bounds__(256) void bsr_thin16_f32(const float* __restrict__ 
             for (int u = 0; u < U; ++u)
                 if (pb + 4 * u + pp >= qe) { wv[u] = 0.f; col[u] = 0; }   // contributes nothing
         }
-        float xv[U][SUBS];
+        f32x4 xv[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const unsigned off = (unsigned)col[u] * row_bytes + lane_x;
-#pragma unroll
-            for (int s = 0; s < SUBS; ++s) xv[u][s] = *reinterpret_cast<const float*>(xt_bytes + off + s * 64);
-        }
+        for (int u = 0; u < U; ++u)
+            xv[u] = *reinterpret_cast<const f32x4*>(xt_bytes + ((unsigned)col[u] * row_bytes + lane_x));
         // groups past the share multiply zeros (wv = 0, col = 0): no branch around the MFMAs, so the
         // accumulators stay where they are
 #pragma unroll
@@ -148,7 +150,7 @@ __global__ __launch_bounds__(256) void bsr_thin16_f32(const float* __restrict__ 
 #pragma unroll
     for (int s = 0; s < SUBS; ++s)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) red[wave][s * 16 + 4 * pp + j][lo] = acc[s][j];
+        for (int j = 0; j < 4; ++j) red[wave][16 * pp + 4 * j + s][lo] = acc[s][j];
     __syncthreads();
 
     // thread t: row t/4 of the tile, columns (t%4)*4 .. +3; 4 adjacent lanes write one row's 64 bytes
@@ -165,8 +167,9 @@ bool mfma_thin_supports(const bsr_matrix* W) { return W->bs_r == 16 && W->bs_c =
 
 size_t mfma_thin_scratch_bytes(const bsr_matrix* W, int64_t m)
 {
-    // m*k floats plus 256 bytes of tail padding (the last tile's gathers may run past the last row)
-    return mfma_thin_supports(W) ? (((size_t)m * (size_t)W->k * sizeof(float) + 256 + 255) & ~(size_t)255) : 0;
+    // k rows of m floats, each padded to a multiple of 4, plus 256 bytes of tail padding (the last
+    // tile's gathers may run past the last row)
+    return mfma_thin_supports(W) ? (((size_t)((m + 3) & ~(int64_t)3) * (size_t)W->k * sizeof(float) + 256 + 255) & ~(size_t)255) : 0;
 }
 
 bsr_status launch_mfma_thin(const spmm_args& a, const tune_opts& tune)
@@ -175,10 +178,10 @@ bsr_status launch_mfma_thin(const spmm_args& a, const tune_opts& tune)
     if (!mfma_thin_supports(W) || a.y_dtype != BSR_F32) return BSR_ERR_UNSUPPORTED;
     const int m = (int)a.m, n = (int)W->n, k = (int)W->k, R = W->R;
     if (!W->scratch || W->scratch_bytes < mfma_thin_scratch_bytes(W, a.m)) return BSR_ERR_WORKSPACE;
-    if (a.m * W->k >= ((int64_t)1 << 30)) return BSR_ERR_SHAPE;      // byte offsets into XT are 32-bit
+    if ((a.m + 3) * W->k >= ((int64_t)1 << 30)) return BSR_ERR_SHAPE;      // byte offsets into XT are 32-bit
     float* XT = static_cast<float*>(W->scratch);
     hipLaunchKernelGGL(transpose_f32, dim3((k + 63) / 64, (m + 31) / 32), dim3(256), 0, a.stream,
-                       (const float*)a.X, XT, m, k);
+                       (const float*)a.X, XT, m, k, (m + 3) & ~3);
     if (hipGetLastError() != hipSuccess) return BSR_ERR_HIP;
     auto go = [&](auto u_tag) -> bsr_status {
         constexpr int U = decltype(u_tag)::value;
