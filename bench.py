@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of bsr_spmm on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-all-configs] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-all-configs] [--no-cpu] [--paper-grid]
 
 A step is one whole product Y = X * W^T (one bsr_spmm call) on the headline workload, the
 "Transformer FFN weight" configuration (fp32, m=128, k=n=3072, 32x32 blocks, density 0.10), with
@@ -140,6 +140,36 @@ def _launch_floor(steps, graph_chunk):
     return ev / steps
 
 
+# The paper's Table 2, column "PRWB+AT" (its tuned kernel on an NVIDIA T4), in microseconds, keyed by
+# (m, k, n, block size) with the three sparsities 0.8 / 0.85 / 0.95 -- context beside our numbers for
+# the same shapes, another machine's and not a target.
+PAPER_TABLE2_T4_US = {
+    (1, 128, 768, 8): (5.1, 3.6, 3.6), (1, 128, 768, 16): (4.0, 3.7, 3.7), (1, 128, 768, 32): (3.6, 3.6, 3.7),
+    (8, 128, 768, 8): (10.0, 8.5, 5.1), (8, 128, 768, 16): (7.0, 8.3, 4.7), (8, 128, 768, 32): (10.0, 4.3, 4.8),
+    (1, 1024, 1024, 8): (13.0, 11.0, 5.9), (1, 1024, 1024, 16): (13.0, 11.0, 5.8), (1, 1024, 1024, 32): (12.0, 4.7, 4.2),
+    (8, 1024, 1024, 8): (78.0, 61.0, 26.0), (8, 1024, 1024, 16): (74.0, 58.0, 25.0), (8, 1024, 1024, 32): (18.0, 17.0, 14.0),
+}
+
+
+def _paper_grid(steps, chunk):
+    """The shape grid of the paper's Tables 1 and 2 (m = 1 and 8, fp32, square blocks 8/16/32, block
+    sparsity 0.8/0.85/0.95) on synthetic patterns of the same density: microseconds per product."""
+    import workloads as wl
+    import paper_2007_13055_amd as lib
+    rows = []
+    for (m, k, n, bs, sp) in wl.paper_grid():
+        p = wl.paper_grid_problem(m, k, n, bs, sp)
+        W, X, Y = _upload(p)
+        _, ev, _ = _time_steps(lambda: lib.bsr_spmm(W, X, Y), steps, 20, chunk)
+        s = ev / steps
+        t4 = PAPER_TABLE2_T4_US[(m, k, n, bs)][(0.8, 0.85, 0.95).index(sp)]
+        rows.append({"m": m, "k": k, "n": n, "bs": bs, "sparsity": sp, "us_per_call": s * 1e6,
+                     "gflops": p.flops / s / 1e9, "path": {1: "wave", 2: "mfma"}[lib.bsr_query_path(W, m)],
+                     "paper_t4_us": t4})
+        del W
+    return rows
+
+
 def _cpu_baseline(p, repeats=5):
     import oracle
     best = float("inf")
@@ -161,6 +191,8 @@ def main():
                     help="launches per captured HIP graph (0 = plain launches only)")
     ap.add_argument("--no-all-configs", action="store_true", help="skip the per-configuration table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--paper-grid", action="store_true",
+                    help="also time the 36 cells of the paper's own shape grid (m = 1, 8) and add them as 'paper_grid'")
     ap.add_argument("--workload", default="ffn", choices=["tiny", "ffn", "batched", "thin", "skewed"],
                     help="workload of the headline line (default: the FFN configuration); the others are for "
                          "profiling one kernel at a time")
@@ -222,6 +254,8 @@ def main():
                              "eager_us_per_call": rq["eager_wall_s"] / steps * 1e6}
             del Wq
         out["per_config"] = table
+    if a.paper_grid:
+        out["paper_grid"] = _paper_grid(a.steps, chunk)
     print(json.dumps(out))
 
 

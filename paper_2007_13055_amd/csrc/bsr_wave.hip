@@ -7,6 +7,8 @@
 // added across lanes at the end.  Where the paper uses a shared-memory tree (or __shfl_down for
 // 32 threads), a wave64 sums through DPP row operations and one ds_swizzle, without touching
 // LDS memory.
+#include <type_traits>
+
 #include "bsr_internal.h"
 
 namespace {
@@ -45,24 +47,34 @@ __device__ __forceinline__ float wave_sum(float v)
     return lo + hi;
 }
 
-// One wavefront per output column j and per group of TM rows of X.
-//   column j = r*bs_r + a; the lanes stride over e = (p - p0)*bs_c + c, i.e. over row a of every
-//   stored block of block-row r in storage order; each lane keeps TM partial sums.
+// One wavefront per output column and per group of TM rows of X.
+//   The wavefront takes row a of the block-row in plan slot s (longest block-rows first): output
+//   column j = r*bs_r + a.  The lanes stride over the elements (p - p0)*bs_c + c of row a of every
+//   stored block of block-row r, in storage order and VEC consecutive elements at a time (one
+//   16-byte load per lane for W and for each row of X when bs_c allows, else single elements); each
+//   lane keeps TM partial sums.
+//   The slot's row descriptor holds the block-row, its first block, its count and its first
+//   block-columns, so the block-column of a lane's elements comes from the same 128 bytes as the
+//   row bounds; longer block-rows read block_indices for the rest.
 // Any block shape, any m.  A block-row without stored blocks leaves the partial sums at zero.
-template <typename T, typename O, int TM>
+template <typename T, typename O, int TM, int VEC>
 __global__ __launch_bounds__(256) void bsr_wave_generic(const T* __restrict__ X, const T* __restrict__ data,
                                                         const int32_t* __restrict__ indices,
-                                                        const int32_t* __restrict__ indptr, O* __restrict__ Y,
+                                                        const int32_t* __restrict__ row_desc, O* __restrict__ Y,
                                                         int m, int k, int n, int bs_r, int bs_c, int col_groups)
 {
+    struct alignas(sizeof(T) * VEC) vec_t { T v[VEC]; };
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int j = (int)(blockIdx.x % (unsigned)col_groups) * 4 + wave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int js = (int)(blockIdx.x % (unsigned)col_groups) * 4 + wave;     // slot*bs_r + a
     const int i0 = (int)(blockIdx.x / (unsigned)col_groups) * TM;
-    if (j >= n) return;                              // whole wave leaves together; no barrier in this kernel
-    const int r = j / bs_r, a = j - r * bs_r;
-    const int p0 = indptr[r], p1 = indptr[r + 1];
-    const int len = (p1 - p0) * bs_c;
+    if (js >= n) return;                             // whole wave leaves together; no barrier in this kernel
+    const int slot = js / bs_r, a = js - slot * bs_r;
+    const int32_t* __restrict__ desc = row_desc + (size_t)slot * kRowDescWords;
+    const int r = desc[0], p0 = desc[1];
+    const int vpr = bs_c / VEC;                      // VEC-element pieces per block row
+    const int len = desc[2] * vpr;
+    const int j = r * bs_r + a;
 
     const T* xrow[TM];
 #pragma unroll
@@ -73,12 +85,17 @@ __global__ __launch_bounds__(256) void bsr_wave_generic(const T* __restrict__ X,
     for (int t = 0; t < TM; ++t) acc[t] = 0.f;
 
     for (int e = lane; e < len; e += 64) {
-        const int q = e / bs_c, c = e - q * bs_c;
+        const int q = e / vpr, c = (e - q * vpr) * VEC;
         const int p = p0 + q;
-        const float w = to_f32(data[((size_t)p * bs_r + a) * bs_c + c]);
-        const int col = indices[p] * bs_c + c;
+        const vec_t w = *reinterpret_cast<const vec_t*>(data + ((size_t)p * bs_r + a) * bs_c + c);
+        const int col = (q < kRowDescCols ? desc[kRowDescColsAt + q] : indices[p]) * bs_c + c;
+        vec_t x[TM];
 #pragma unroll
-        for (int t = 0; t < TM; ++t) acc[t] = fmaf(to_f32(xrow[t][col]), w, acc[t]);
+        for (int t = 0; t < TM; ++t) x[t] = *reinterpret_cast<const vec_t*>(xrow[t] + col);
+#pragma unroll
+        for (int t = 0; t < TM; ++t)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[t] = fmaf(to_f32(x[t].v[v]), to_f32(w.v[v]), acc[t]);
     }
 #pragma unroll
     for (int t = 0; t < TM; ++t) {
@@ -93,20 +110,31 @@ bsr_status launch_generic(const spmm_args& a)
     const bsr_matrix* W = a.W;
     const int m = (int)a.m, n = (int)W->n, k = (int)W->k;
     const int col_groups = (n + 3) / 4;
-    auto go = [&](auto tm_tag) -> bsr_status {
-        constexpr int TM = decltype(tm_tag)::value;
+    auto go = [&](auto tm_tag, auto vec_tag) -> bsr_status {
+        constexpr int TM = decltype(tm_tag)::value, VEC = decltype(vec_tag)::value;
         const int64_t row_groups = (m + TM - 1) / TM;
         const int64_t blocks = row_groups * col_groups;
         if (blocks >= ((int64_t)1 << 31) || blocks * 256 >= ((int64_t)1 << 32)) return BSR_ERR_SHAPE;
-        hipLaunchKernelGGL((bsr_wave_generic<T, O, TM>), dim3((unsigned)blocks), dim3(256), 0, a.stream,
-                           (const T*)a.X, (const T*)W->data, W->indices, W->indptr, (O*)a.Y, m, k, n,
+        hipLaunchKernelGGL((bsr_wave_generic<T, O, TM, VEC>), dim3((unsigned)blocks), dim3(256), 0, a.stream,
+                           (const T*)a.X, (const T*)W->data, W->indices, W->row_desc, (O*)a.Y, m, k, n,
                            (int)W->bs_r, (int)W->bs_c, col_groups);
         return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
     };
-    if (m >= 8) return go(std::integral_constant<int, 8>{});
-    if (m >= 4) return go(std::integral_constant<int, 4>{});
-    if (m >= 2) return go(std::integral_constant<int, 2>{});
-    return go(std::integral_constant<int, 1>{});
+    // 16-byte pieces when a block row is made of them (k is a multiple of bs_c and X, W are 16-byte
+    // aligned, so every piece is aligned), single elements otherwise
+    constexpr int V16 = 16 / (int)sizeof(T);
+    const tune_opts tune = read_tune_env();
+    // rows of X per wavefront: 8 amortise the reads of W best when there are many rows; up to m = 8
+    // the wavefronts are few and short, and 4 rows each (twice the wavefronts) finish sooner
+    const int rows = tune.mt > 0 ? tune.mt : (m > 8 ? 8 : (m >= 4 ? 4 : m));
+    auto with_tm = [&](auto vec_tag) -> bsr_status {
+        if (rows >= 8) return go(std::integral_constant<int, 8>{}, vec_tag);
+        if (rows >= 4) return go(std::integral_constant<int, 4>{}, vec_tag);
+        if (rows >= 2) return go(std::integral_constant<int, 2>{}, vec_tag);
+        return go(std::integral_constant<int, 1>{}, vec_tag);
+    };
+    if (W->bs_c % V16 == 0) return with_tm(std::integral_constant<int, V16>{});
+    return with_tm(std::integral_constant<int, 1>{});
 }
 
 }  // namespace
