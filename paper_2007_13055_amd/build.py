@@ -20,6 +20,27 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-
                "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
+# Kernels in these files issue loads from inline assembly and place the waits themselves; the compiler
+# does not know such a register is still being filled, so a spill of one would store garbage.  The
+# build therefore fails if any kernel of these files spills a vector register.
+NO_SPILL = ("bsr_mfma_ksplit.hip", "bsr_mfma_tile.hip")
+
+
+def _spilling_kernels(remarks: str):
+    """Names of kernels whose resource-usage remarks report VGPR spills or scratch memory."""
+    bad, name = [], None
+    for line in remarks.splitlines():
+        if "remark:" not in line:
+            continue
+        text = line.split("remark:", 1)[1].strip()
+        if text.startswith("Function Name:"):
+            name = text.split(":", 1)[1].split("[")[0].strip()
+        elif text.startswith("VGPRs Spill:") or text.startswith("ScratchSize"):
+            if int(text.split(":", 1)[1].split("[")[0].strip()) != 0 and name not in bad:
+                bad.append(name)
+    return bad
+
+
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
@@ -29,7 +50,23 @@ def _compile(src, force):
     deps = [src] + glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
     if not force and os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps):
         return obj
-    r = subprocess.run(["hipcc", *HIPCC_FLAGS, "-c", src, "-o", obj], capture_output=True, text=True)
+    check = os.path.basename(src) in NO_SPILL
+    extra = ["-Rpass-analysis=kernel-resource-usage"] if check else []
+    r = subprocess.run(["hipcc", *HIPCC_FLAGS, *extra, "-c", src, "-o", obj], capture_output=True, text=True)
+    if check:
+        bad = _spilling_kernels(r.stderr) if r.returncode == 0 else []
+        if bad:
+            os.remove(obj)
+            raise RuntimeError(f"{src}: kernels with hand-placed loads spill registers: {bad}")
+        keep, skip = [], 0
+        for l in r.stderr.splitlines():          # drop the remarks and the source excerpts printed under them
+            if "kernel-resource-usage" in l:
+                skip = 2
+            elif skip and (l.lstrip().startswith("|") or l.strip()[:1].isdigit()):
+                skip -= 1
+            else:
+                keep.append(l)
+        r.stderr = "\n".join(keep)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")

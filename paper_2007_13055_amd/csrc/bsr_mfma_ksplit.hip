@@ -168,18 +168,28 @@ __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, 
 #pragma unroll
             for (int u = 0; u < NA; ++u) mfma_frag<T, MM, CH>(acc[u], wf[u], xf);
         };
-        // every load issued below is waited for before the wavefront ends: none is left in flight
-        issue(0, wave);
-        bool odd = wave + nw < cnt;                             // set 1 holds a block (all uniform)
-        if (odd) issue(1, wave + nw);
-        for (int j = wave; j < cnt; j += 2 * nw) {
-            consume(0, odd);
-            const bool next = j + 2 * nw < cnt;
-            if (next) issue(0, j + 2 * nw);
-            if (odd) {
-                consume(1, next);
-                odd = j + 3 * nw < cnt;
-                if (odd) issue(1, j + 3 * nw);
+        // every load issued below is waited for before the wavefront ends: none is left in flight.
+        // Two register sets only where both fit the register file: the loads are written in
+        // assembly, so a spill of a register a load has not filled yet would store garbage.
+        constexpr bool kTwoSets = NLW + NLX <= 12;
+        if constexpr (kTwoSets) {
+            issue(0, wave);
+            bool odd = wave + nw < cnt;                         // set 1 holds a block (all uniform)
+            if (odd) issue(1, wave + nw);
+            for (int j = wave; j < cnt; j += 2 * nw) {
+                consume(0, odd);
+                const bool next = j + 2 * nw < cnt;
+                if (next) issue(0, j + 2 * nw);
+                if (odd) {
+                    consume(1, next);
+                    odd = j + 3 * nw < cnt;
+                    if (odd) issue(1, j + 3 * nw);
+                }
+            }
+        } else {
+            for (int j = wave; j < cnt; j += nw) {
+                issue(0, j);
+                consume(0, false);
             }
         }
         wait_loads<0>();

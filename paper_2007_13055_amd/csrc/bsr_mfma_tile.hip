@@ -285,9 +285,11 @@ bsr_status launch_tile_shape(const spmm_args& a, const tune_opts& tune)
             if (depth == 3) return go(std::integral_constant<int, 1>{}, std::integral_constant<int, 3>{});
             return go(std::integral_constant<int, 1>{}, std::integral_constant<int, 4>{});
         }
+        // two tiles along m: at most two blocks in flight -- a third does not fit the register file for
+        // the largest fp32 blocks, and the loads are written in assembly, so a spilled register that a
+        // load has not filled yet would store garbage
         if (depth == 1) return go(std::integral_constant<int, 2>{}, std::integral_constant<int, 1>{});
-        if (depth == 2) return go(std::integral_constant<int, 2>{}, std::integral_constant<int, 2>{});
-        return go(std::integral_constant<int, 2>{}, std::integral_constant<int, 3>{});
+        return go(std::integral_constant<int, 2>{}, std::integral_constant<int, 2>{});
     }
 }
 

@@ -57,6 +57,23 @@ def test_wave_path_block_shapes(oracle_mod, dtype, bs):
             assert np.array_equal(wl.round_to_storage(Yg32.astype(np.float32), dtype).astype(np.float64), Yg)
 
 
+@pytest.mark.parametrize("rows", [0, 1, 2, 4, 8])
+@pytest.mark.parametrize("dtype,bs", [("f32", (8, 8)), ("f32", (16, 2)), ("f16", (4, 8)), ("bf16", (32, 32))])
+def test_wave_path_rows_per_wavefront_and_long_rows(oracle_mod, monkeypatch, rows, dtype, bs):
+    """The wave path at every rows-per-wavefront setting (mt), with 16-byte and single-element loads, a
+    block-row longer than a row descriptor's inline block-columns (40 > 28), and empty block-rows."""
+    if rows:
+        monkeypatch.setenv("BSR_SPMM_TUNE", f"mt={rows}")
+    bs_r, bs_c = bs
+    counts = np.array([0, 40, 1, 29, 0, 28, 7])
+    for m in (1, 5, 8, 13):
+        p = wl.make_problem("wl", m, 40 * bs_c, counts.shape[0] * bs_r, bs_r, bs_c, dtype, dtype, ("counts", counts),
+                            ("normal", 1.0), ("normal", 1.0), 700 + m + bs_r)
+        Yo, So = oracle_of(oracle_mod, p)
+        Yg, _ = gpu_product(p, path=WAVE)
+        check(Yg, Yo, So, p.tau, f"wave rows={rows} {dtype} {bs} m={m}", out_dtype=dtype)
+
+
 # ------------------------------------------------------------------ the five configurations, full size
 @pytest.mark.parametrize("cid", [1, 2, 3, 4])
 def test_config_full_size_auto_path(oracle_mod, cid):
@@ -234,9 +251,11 @@ def test_repeat_calls_are_bitwise_identical(oracle_mod):
 
 # ------------------------------------------------------------------ every matrix-core kernel variant
 # BSR_SPMM_TUNE is the library's development knob; "variant" pins the matrix-core kernel:
-# 1 direct (operands from global memory), 2 k-split (few rows of X), 3 LDS-staged tiles (many rows).
-@pytest.mark.parametrize("variant,extra", [(1, ""), (1, ",mt=2,nw=4"), (2, ""), (2, ",nw=3,a=1"), (3, ",mt=1,a=1"),
-                                           (3, ",mt=1,a=3"), (3, ",mt=2,a=2"), (3, ",mt=1,a=2,b=3")])
+# 1 direct (operands from global memory), 2 k-split (few rows of X; mt=1 / mt=2: 16- / 32-row tiles,
+# nw wavefronts, a blocks per wavefront), 3 LDS-staged tiles (many rows).
+@pytest.mark.parametrize("variant,extra", [(1, ""), (1, ",mt=2,nw=4"), (2, ""), (2, ",nw=3,a=1"), (2, ",mt=1"),
+                                           (2, ",mt=2,nw=8"), (2, ",mt=1,nw=2,a=1"), (2, ",mt=2,a=3"),
+                                           (3, ",mt=1,a=1"), (3, ",mt=1,a=3"), (3, ",mt=2,a=2"), (3, ",mt=1,a=2,b=3")])
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 def test_mfma_kernel_variants(oracle_mod, monkeypatch, variant, extra, dtype):
     monkeypatch.setenv("BSR_SPMM_TUNE", f"variant={variant}{extra}")
@@ -252,6 +271,24 @@ def test_mfma_kernel_variants(oracle_mod, monkeypatch, variant, extra, dtype):
             check(Yg, Yo, So, p.tau, f"variant {variant}{extra} {dtype} {bs_r}x{bs_c} m={m}", out_dtype=dtype)
             Yg2, _ = gpu_product(p, path=MFMA, W=W)
             assert np.array_equal(Yg, Yg2), "two runs differ: race"
+
+
+@pytest.mark.parametrize("tile_rows", [1, 2])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("bs", SHAPES)
+def test_ksplit_kernel_every_shape_both_tile_heights(oracle_mod, monkeypatch, tile_rows, dtype, bs):
+    """variant 2 for every supported block shape and type at 16-row (mt=1) and 32-row (mt=2) tiles: one
+    block-row longer than a descriptor's inline block-columns, one empty, a ragged last m-tile."""
+    monkeypatch.setenv("BSR_SPMM_TUNE", f"variant=2,mt={tile_rows}")
+    bs_r, bs_c = bs
+    counts = np.array([3, 0, 31, 8, 1])
+    p = wl.make_problem("ks", 45, 32 * bs_c, counts.shape[0] * bs_r, bs_r, bs_c, dtype, dtype, ("counts", counts),
+                        ("normal", 1.0), ("normal", 1.0), 800 + bs_r + bs_c)
+    Yo, So = oracle_of(oracle_mod, p)
+    Yg, W = gpu_product(p, path=MFMA)
+    check(Yg, Yo, So, p.tau, f"k-split mt={tile_rows} {dtype} {bs}", out_dtype=dtype)
+    Yg2, _ = gpu_product(p, path=MFMA, W=W)
+    assert np.array_equal(Yg, Yg2), "two runs differ: race"
 
 
 def test_tile_kernel_small_integers_bitwise(oracle_mod, monkeypatch):
