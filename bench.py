@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of bsr_spmm on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-all-configs] [--no-cpu] [--paper-grid]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-all-configs] [--no-cpu] [--paper-grid] [--peaks]
 
 A step is one whole product Y = X * W^T (one bsr_spmm call) on the headline workload, the
 "Transformer FFN weight" configuration (fp32, m=128, k=n=3072, 32x32 blocks, density 0.10), with
@@ -170,6 +170,27 @@ def _paper_grid(steps, chunk):
     return rows
 
 
+def _measured_peaks():
+    """What this machine delivers on plain library work, for context beside the published peaks the roofline
+    uses: a 1 GiB device-to-device copy (read + written bytes per second) and large dense GEMMs through
+    torch (rocBLAS / hipBLASLt).  Library figures, not limits."""
+    import torch
+    out = {}
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    _, ev, _ = _time_steps(lambda: dst.copy_(src), 20, 3, 0)
+    out["copy_1GiB_GBs"] = 2 * src.numel() * 4 / (ev / 20) / 1e9
+    del src, dst
+    for name, dt, nn in (("gemm_f32_8192_TFLOPs", torch.float32, 8192), ("gemm_bf16_8192_TFLOPs", torch.bfloat16, 8192)):
+        a = torch.randn(nn, nn, device="cuda", dtype=dt)
+        b = torch.randn(nn, nn, device="cuda", dtype=dt)
+        c = torch.empty(nn, nn, device="cuda", dtype=dt)
+        _, ev, _ = _time_steps(lambda: torch.mm(a, b, out=c), 10, 3, 0)
+        out[name] = 2 * nn ** 3 / (ev / 10) / 1e12
+        del a, b, c
+    return out
+
+
 def _cpu_baseline(p, repeats=5):
     import oracle
     best = float("inf")
@@ -191,6 +212,8 @@ def main():
                     help="launches per captured HIP graph (0 = plain launches only)")
     ap.add_argument("--no-all-configs", action="store_true", help="skip the per-configuration table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--peaks", action="store_true",
+                    help="also time a 1 GiB copy and two large torch GEMMs on this box and add them as 'measured_peaks'")
     ap.add_argument("--paper-grid", action="store_true",
                     help="also time the 36 cells of the paper's own shape grid (m = 1, 8) and add them as 'paper_grid'")
     ap.add_argument("--workload", default="ffn", choices=["tiny", "ffn", "batched", "thin", "skewed"],
@@ -256,6 +279,8 @@ def main():
         out["per_config"] = table
     if a.paper_grid:
         out["paper_grid"] = _paper_grid(a.steps, chunk)
+    if a.peaks:
+        out["measured_peaks"] = _measured_peaks()
     print(json.dumps(out))
 
 
