@@ -141,15 +141,40 @@ bsr_status bsr_scratch_size(const bsr_matrix* W, int64_t m, size_t* bytes);
 bsr_status bsr_set_scratch(bsr_matrix* W, void* scratch_dev, size_t bytes);
 
 /*
- * As bsr_spmm() with the kernel family fixed.  BSR_PATH_MFMA needs bs_r in {16, 32, 64},
- * bs_c a multiple of 16 up to 128 (16-bit types) or of 8 up to 64 (fp32), or the thin shape
- * bs_c == 1 with bs_r == 16 and fp32; otherwise BSR_ERR_UNSUPPORTED.  BSR_PATH_WAVE takes
- * any shape.
+ * As bsr_spmm() with the kernel family fixed.  BSR_PATH_MFMA needs bs_r and bs_c in {16, 32, 64},
+ * or the thin shape bs_c == 1 with bs_r == 16 and fp32; otherwise BSR_ERR_UNSUPPORTED.
+ * BSR_PATH_WAVE takes any shape.
  */
 bsr_status bsr_spmm_ex(const bsr_matrix* W, int64_t m, const void* X_dev, void* Y_dev,
                        bsr_dtype y_dtype, bsr_path path, void* hip_stream);
 
-/* The path BSR_PATH_AUTO resolves to for this handle and m (never AUTO).  Errors: NULL. */
+/*
+ * Plan-time tuning by timed trials ("Automatic parameter tuning": the paper picks its kernels'
+ * parameters per input shape by running the candidates).  Runs the product for every candidate
+ * kernel and setting the library has for this W, this m and this output type -- 2 warm-up and
+ * `trials` timed launches each (trials < 1: 20), timed with events on `hip_stream` -- and remembers
+ * the fastest in the handle: later bsr_spmm() / BSR_PATH_AUTO calls with the same m and y_dtype use
+ * it.  Every candidate computes the same product, so Y_dev holds Y = X * W^T afterwards.
+ *   X_dev, Y_dev  as for bsr_spmm(); their values do not change which kernel is fastest
+ *   tried_out     (may be NULL) number of candidates that ran
+ *   best_us_out   (may be NULL) microseconds per product of the one remembered
+ * Waits for the stream (it is not asynchronous) and must not run concurrently with other calls on
+ * the same handle.  Lend scratch first (bsr_set_scratch) if kernels that need it should compete.
+ * Errors: as bsr_spmm(); on error nothing is remembered.
+ */
+bsr_status bsr_tune(bsr_matrix* W, int64_t m, const void* X_dev, void* Y_dev, bsr_dtype y_dtype,
+                    int trials, void* hip_stream, int* tried_out, float* best_us_out);
+
+/*
+ * What bsr_tune() remembered for (m, y_dtype): settings_out = {kernel family (bsr_path), matrix-core
+ * kernel variant (0 the library's choice, 1 direct, 2 k-split, 3 LDS tiles, 4 LDS stripe), wavefronts
+ * per workgroup, tile setting, two per-variant settings}, 0 = the kernel's default; us_out (may be
+ * NULL) its measured microseconds per product.  BSR_ERR_UNSUPPORTED if nothing is remembered.
+ */
+bsr_status bsr_tune_result(const bsr_matrix* W, int64_t m, bsr_dtype y_dtype, int32_t settings_out[6], float* us_out);
+
+/* The path BSR_PATH_AUTO resolves to for this handle and m (never AUTO; what bsr_tune()
+ * remembered is not consulted).  Errors: NULL. */
 bsr_status bsr_query_path(const bsr_matrix* W, int64_t m, bsr_path* path_out);
 
 /* Static, human-readable text for a status code. */

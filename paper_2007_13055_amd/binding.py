@@ -47,6 +47,9 @@ def load_library():
     lib.bsr_spmm.argtypes = [vp, i64, vp, vp, ctypes.c_int, vp]
     lib.bsr_spmm_ex.argtypes = [vp, i64, vp, vp, ctypes.c_int, ctypes.c_int, vp]
     lib.bsr_query_path.argtypes = [vp, i64, ctypes.POINTER(ctypes.c_int)]
+    lib.bsr_tune.argtypes = [vp, i64, vp, vp, ctypes.c_int, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_int),
+                             ctypes.POINTER(ctypes.c_float)]
+    lib.bsr_tune_result.argtypes = [vp, i64, ctypes.c_int, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float)]
     lib.bsr_scratch_size.argtypes = [vp, i64, ctypes.POINTER(sz)]
     lib.bsr_set_scratch.argtypes = [vp, vp, sz]
     lib.bsr_status_string.argtypes = [ctypes.c_int]
@@ -189,6 +192,40 @@ def bsr_spmm_ex(W: BsrMatrix, X, Y=None, y_dtype=None, path=PATH_AUTO):
 
 def bsr_spmm(W: BsrMatrix, X, Y=None, y_dtype=None):
     return bsr_spmm_ex(W, X, Y, y_dtype, PATH_AUTO)
+
+
+def bsr_tune(W: BsrMatrix, X, Y=None, y_dtype=None, trials: int = 20):
+    """Times the library's candidate kernels for this W, X.shape[0] and output type on torch's current
+    stream and makes later bsr_spmm calls of that size use the fastest.  Returns (candidates tried,
+    microseconds per product of the fastest).  Waits for the stream."""
+    import torch
+    if X.dim() != 2 or X.shape[1] != W.k or _dtype_name(X) != W.dtype or not X.is_contiguous():
+        raise ValueError("X must be a contiguous (m, k) tensor of W's dtype")
+    y_dtype = y_dtype or W.dtype
+    m = int(X.shape[0])
+    W.ensure_scratch(m)
+    if Y is None:
+        Y = torch.empty((m, W.n), dtype=_torch_dtype(y_dtype), device=X.device)
+    elif tuple(Y.shape) != (m, W.n) or _dtype_name(Y) != y_dtype or not Y.is_contiguous():
+        raise ValueError("Y must be a contiguous (m, n) tensor of y_dtype")
+    tried, best = ctypes.c_int(0), ctypes.c_float(0.0)
+    st = load_library().bsr_tune(W.handle, m, X.data_ptr(), Y.data_ptr(), _DTYPE_CODE[y_dtype], int(trials),
+                                 torch.cuda.current_stream().cuda_stream, ctypes.byref(tried), ctypes.byref(best))
+    if st != 0:
+        raise BsrError(st, "bsr_tune")
+    return int(tried.value), float(best.value)
+
+
+def bsr_tune_result(W: BsrMatrix, m: int, y_dtype=None):
+    """What bsr_tune remembered for (m, y_dtype): dict of settings and microseconds, or None."""
+    out, us = (ctypes.c_int32 * 6)(), ctypes.c_float(0.0)
+    st = load_library().bsr_tune_result(W.handle, m, _DTYPE_CODE[y_dtype or W.dtype], out, ctypes.byref(us))
+    if st == 9:
+        return None
+    if st != 0:
+        raise BsrError(st, "bsr_tune_result")
+    keys = ("path", "variant", "nw", "mt", "a", "b")
+    return {**{k: int(v) for k, v in zip(keys, out)}, "us": float(us.value)}
 
 
 def bsr_scratch_size(W: BsrMatrix, m: int) -> int:

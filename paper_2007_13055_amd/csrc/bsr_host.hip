@@ -1,11 +1,13 @@
 // Host side of libbsr_spmm: structural validation, the block-row plan, handle life cycle and
 // kernel-family dispatch.  Nothing here allocates device memory.
 #include <algorithm>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <string>
 #include <new>
 #include <numeric>
+#include <utility>
 
 #include "bsr_internal.h"
 
@@ -50,6 +52,7 @@ tune_opts read_tune_env()
     tune_opts t;
     const char* e = std::getenv("BSR_SPMM_TUNE");
     if (!e) return t;
+    t.from_env = true;
     std::string s(e);
     size_t pos = 0;
     while (pos < s.size()) {
@@ -306,25 +309,149 @@ bsr_status bsr_set_scratch(bsr_matrix* W, void* scratch_dev, size_t bytes)
     return BSR_OK;
 }
 
-bsr_status bsr_spmm_ex(const bsr_matrix* W, int64_t m, const void* X_dev, void* Y_dev,
-                       bsr_dtype y_dtype, bsr_path path, void* hip_stream)
+namespace {
+
+bsr_status check_product_args(const bsr_matrix* W, int64_t m, const void* X_dev, const void* Y_dev, bsr_dtype y_dtype)
 {
     if (!W) return BSR_ERR_NULL;
     if (m < 0) return BSR_ERR_SHAPE;
     if (y_dtype != W->dtype && y_dtype != BSR_F32) return BSR_ERR_DTYPE;
-    if (path != BSR_PATH_AUTO && path != BSR_PATH_WAVE && path != BSR_PATH_MFMA) return BSR_ERR_UNSUPPORTED;
     if (m == 0 || W->n == 0) return BSR_OK;
     if (!Y_dev || (W->k > 0 && !X_dev)) return BSR_ERR_NULL;
     if (m * std::max<int64_t>(W->k, W->n) >= kInt32Limit) return BSR_ERR_SHAPE;
     if (!aligned16(X_dev) || !aligned16(Y_dev)) return BSR_ERR_ALIGN;
-    if (path == BSR_PATH_AUTO) bsr_query_path(W, m, &path);
-    spmm_args a{W, m, X_dev, Y_dev, y_dtype, (hipStream_t)hip_stream};
+    return BSR_OK;
+}
+
+// One product on a fixed family (never AUTO) with fixed settings.
+bsr_status run_product(const spmm_args& a, bsr_path path, const tune_opts& t)
+{
     if (path == BSR_PATH_MFMA) {
-        if (mfma_thin_supports(W)) return launch_mfma_thin(a, read_tune_env());
-        if (!mfma_supports(W)) return BSR_ERR_UNSUPPORTED;
-        return launch_mfma(a);
+        if (mfma_thin_supports(a.W)) return launch_mfma_thin(a, t);
+        if (!mfma_supports(a.W)) return BSR_ERR_UNSUPPORTED;
+        return launch_mfma(a, t);
     }
-    return launch_wave(a);
+    return launch_wave(a, t);
+}
+
+}  // namespace
+
+bsr_status bsr_spmm_ex(const bsr_matrix* W, int64_t m, const void* X_dev, void* Y_dev,
+                       bsr_dtype y_dtype, bsr_path path, void* hip_stream)
+{
+    if (path != BSR_PATH_AUTO && path != BSR_PATH_WAVE && path != BSR_PATH_MFMA) return BSR_ERR_UNSUPPORTED;
+    const bsr_status st = check_product_args(W, m, X_dev, Y_dev, y_dtype);
+    if (st != BSR_OK || m == 0 || W->n == 0) return st;
+    tune_opts t = read_tune_env();
+    if (path == BSR_PATH_AUTO) {
+        bool tuned = false;
+        if (!t.from_env) {                            // what bsr_tune() remembered for this m, if anything
+            std::lock_guard<std::mutex> lock(W->tune_mu);
+            auto it = W->tuned.find({m, (int)y_dtype});
+            if (it != W->tuned.end()) { path = it->second.path; t = it->second.opts; tuned = true; }
+        }
+        // a remembered thin-block choice needs its scratch still lent
+        if (tuned && path == BSR_PATH_MFMA && mfma_thin_supports(W) &&
+            (!W->scratch || W->scratch_bytes < mfma_thin_scratch_bytes(W, m))) tuned = false;
+        if (!tuned) { bsr_query_path(W, m, &path); if (!t.from_env) t = tune_opts{}; }
+    }
+    return run_product(spmm_args{W, m, X_dev, Y_dev, y_dtype, (hipStream_t)hip_stream}, path, t);
+}
+
+// Candidate settings per kernel family for this W and m (the search space of bsr_tune).
+static std::vector<tuned_choice> tune_candidates(const bsr_matrix* W, int64_t m)
+{
+    std::vector<tuned_choice> c;
+    auto add = [&](bsr_path path, int variant, int nw, int mt, int a, int b) {
+        tuned_choice t;
+        t.path = path;
+        t.opts.variant = variant; t.opts.nw = nw; t.opts.mt = mt; t.opts.a = a; t.opts.b = b;
+        c.push_back(t);
+    };
+    const bool thin = mfma_thin_supports(W);
+    if (thin) {
+        if (W->scratch && W->scratch_bytes >= mfma_thin_scratch_bytes(W, m) && m >= 16)
+            for (int a : {4, 6, 8, 10, 12, 14, 16}) add(BSR_PATH_MFMA, 0, 0, 0, a, 0);
+    } else if (mfma_supports(W) && m >= 8) {
+        add(BSR_PATH_MFMA, 0, 0, 0, 0, 0);                                  // the library's own choice
+        for (int mt : {1, 2}) {
+            if (mt == 2 && W->bs_r < 32) continue;
+            for (int nw : {2, 4, 8})
+                for (int per : {1, 2, 4}) add(BSR_PATH_MFMA, 2, nw, mt, per, 0);
+        }
+        if (W->bs_r >= 32 && m >= 128) {
+            for (int depth : {2, 3, 4}) add(BSR_PATH_MFMA, 3, 0, 1, depth, 0);
+            for (int depth : {1, 2}) add(BSR_PATH_MFMA, 3, 0, 2, depth, 0);
+        }
+        for (int tm : {1, 2, 4})
+            if (m >= 16 * tm && mfma_stripe_supports(W, 16 * tm)) add(BSR_PATH_MFMA, 4, 0, tm, 0, 0);
+        add(BSR_PATH_MFMA, 1, 0, 0, 0, 0);
+        if (W->bs_r >= 32) add(BSR_PATH_MFMA, 1, 4, 2, 0, 0);
+    }
+    if (m <= 64 || c.empty())                                               // the wavefront-reduction family
+        for (int rows : {1, 2, 4, 8})
+            if (rows <= std::max<int64_t>(m, 1) || rows == 1) add(BSR_PATH_WAVE, 0, 0, rows, 0, 0);
+    return c;
+}
+
+bsr_status bsr_tune(bsr_matrix* W, int64_t m, const void* X_dev, void* Y_dev, bsr_dtype y_dtype,
+                    int trials, void* hip_stream, int* tried_out, float* best_us_out)
+{
+    if (tried_out) *tried_out = 0;
+    if (best_us_out) *best_us_out = 0.f;
+    const bsr_status st = check_product_args(W, m, X_dev, Y_dev, y_dtype);
+    if (st != BSR_OK || m == 0 || W->n == 0) return st;
+    if (trials < 1) trials = 20;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const spmm_args a{W, m, X_dev, Y_dev, y_dtype, stream};
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess) return BSR_ERR_HIP;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return BSR_ERR_HIP; }
+    tuned_choice best;
+    int tried = 0;
+    const bool verbose = std::getenv("BSR_TUNE_VERBOSE") != nullptr;   // one line per candidate on stderr
+    bsr_status result = BSR_OK;
+    for (tuned_choice cand : tune_candidates(W, m)) {
+        bsr_status s = BSR_OK;
+        for (int i = 0; i < 2 && s == BSR_OK; ++i) s = run_product(a, cand.path, cand.opts);     // warm-up
+        if (s == BSR_ERR_UNSUPPORTED || s == BSR_ERR_WORKSPACE) continue;                         // not for this shape
+        if (s != BSR_OK) { result = s; break; }
+        if (hipEventRecord(e0, stream) != hipSuccess) { result = BSR_ERR_HIP; break; }
+        for (int i = 0; i < trials && s == BSR_OK; ++i) s = run_product(a, cand.path, cand.opts);
+        if (s != BSR_OK) { result = s; break; }
+        float ms = 0.f;
+        if (hipEventRecord(e1, stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+            hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { result = BSR_ERR_HIP; break; }
+        cand.us = ms * 1000.f / (float)trials;
+        ++tried;
+        if (verbose)
+            std::fprintf(stderr, "[bsr_tune] m=%lld path=%d variant=%d nw=%d mt=%d a=%d b=%d: %.2f us\n", (long long)m,
+                         (int)cand.path, cand.opts.variant, cand.opts.nw, cand.opts.mt, cand.opts.a, cand.opts.b, cand.us);
+        if (best.path == BSR_PATH_AUTO || cand.us < best.us) best = cand;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (result != BSR_OK) return result;
+    if (best.path != BSR_PATH_AUTO) {
+        std::lock_guard<std::mutex> lock(W->tune_mu);
+        W->tuned[{m, (int)y_dtype}] = best;
+    }
+    if (tried_out) *tried_out = tried;
+    if (best_us_out) *best_us_out = best.us;
+    return BSR_OK;
+}
+
+bsr_status bsr_tune_result(const bsr_matrix* W, int64_t m, bsr_dtype y_dtype, int32_t settings_out[6], float* us_out)
+{
+    if (!W || !settings_out) return BSR_ERR_NULL;
+    std::lock_guard<std::mutex> lock(W->tune_mu);
+    auto it = W->tuned.find({m, (int)y_dtype});
+    if (it == W->tuned.end()) return BSR_ERR_UNSUPPORTED;
+    const tuned_choice& c = it->second;
+    const int32_t v[6] = {(int32_t)c.path, c.opts.variant, c.opts.nw, c.opts.mt, c.opts.a, c.opts.b};
+    for (int i = 0; i < 6; ++i) settings_out[i] = v[i];
+    if (us_out) *us_out = c.us;
+    return BSR_OK;
 }
 
 bsr_status bsr_spmm(const bsr_matrix* W, int64_t m, const void* X_dev, void* Y_dev,

@@ -5,6 +5,7 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <map>
 #include <mutex>
 #include <vector>
 
@@ -16,6 +17,25 @@ constexpr int kRowDescColsAt = 4;                 // word index of the first inl
 constexpr int kRowDescCols = kRowDescWords - kRowDescColsAt;
 constexpr int kMaxKsplitItems = 4096;             // the k-split kernel is used below this many (block-row, m-tile) items
 constexpr int kStripeChunkPairs = 6;              // the stripe kernel's pair table lists block-rows in chunks of this many pairs
+
+// Development knobs, read from the environment variable BSR_SPMM_TUNE ("key=value,key=value"), and
+// the settings bsr_tune() remembers per m.  Unset keys are 0 and mean "the library's own choice".
+//   variant  1 direct, 2 ksplit, 3 tile, 4 stripe  (matrix-core kernel variant)
+//   nw       wavefronts per workgroup      mt   MFMA tiles along m per wavefront (wave path: rows of X
+//            per wavefront; ksplit: 1 = 16-row, 2 = 32-row tiles)
+//   a, b     per-variant: ksplit a = blocks per wavefront; tile a = blocks in flight, b-1 = long rows
+//            started first; stripe a = block-row groups; thin a = groups of 4 blocks in flight
+struct tune_opts {
+    int variant = 0, nw = 0, mt = 0, a = 0, b = 0;
+    bool from_env = false;                   // BSR_SPMM_TUNE is set: it overrides what bsr_tune() remembered
+};
+
+// What bsr_tune() found fastest for one m: the kernel family and its settings.
+struct tuned_choice {
+    bsr_path path = BSR_PATH_AUTO;
+    tune_opts opts;
+    float us = 0.f;                          // its measured time per product
+};
 
 // Host-side description of one W.  Device pointers are borrowed from the caller.
 struct bsr_matrix {
@@ -56,6 +76,9 @@ struct bsr_matrix {
     // need beyond X, W and Y (the thin-block path keeps a transposed copy of X there).
     void* scratch = nullptr;
     size_t scratch_bytes = 0;
+    // bsr_tune() results, keyed by (m, output type)
+    mutable std::mutex tune_mu;
+    std::map<std::pair<int64_t, int>, tuned_choice> tuned;
 };
 
 // Arguments every kernel launcher takes.
@@ -68,20 +91,11 @@ struct spmm_args {
     hipStream_t stream;
 };
 
-// Development knobs, read from the environment variable BSR_SPMM_TUNE ("key=value,key=value").
-// Unset keys are 0 and mean "the library's own choice".
-//   variant  1 direct, 2 ksplit, 3 tile, 4 stripe  (matrix-core kernel variant)
-//   nw       wavefronts per workgroup      mt   MFMA tiles along m per wavefront
-//   a, b     per-variant: ksplit a = blocks per wavefront; tile a = blocks in flight, b-1 = long rows
-//            started first; stripe a = block-row groups; thin a = groups of 4 blocks in flight
-struct tune_opts {
-    int variant = 0, nw = 0, mt = 0, a = 0, b = 0;
-};
 tune_opts read_tune_env();
 
 // Each returns BSR_OK, BSR_ERR_UNSUPPORTED (shape not covered by that family) or BSR_ERR_HIP.
-bsr_status launch_wave(const spmm_args& a);
-bsr_status launch_mfma(const spmm_args& a);
+bsr_status launch_wave(const spmm_args& a, const tune_opts& t);
+bsr_status launch_mfma(const spmm_args& a, const tune_opts& t);
 bool mfma_supports(const bsr_matrix* W);
 
 // matrix-core kernel variants (bsr_mfma*.hip)

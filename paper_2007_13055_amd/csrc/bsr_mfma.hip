@@ -157,25 +157,32 @@ bool mfma_supports(const bsr_matrix* W)
 }
 
 // Which matrix-core kernel serves this product.
-//   ksplit  few tiles along m (m/MM small): the stored blocks of a block-row are spread over the
+//   ksplit  fewer than about 6000 (m-tile, block-row) items: the stored blocks of a block-row are spread over the
 //           wavefronts of a workgroup, otherwise most of the chip would idle
 //   tile    many rows of X and blocks at least 32 rows tall: 128 x bs_r tiles of Y, the W block and
 //           the X tile staged in LDS with coalesced reads, XCD-aware launch order
 //   stripe  16x16 blocks of a 16-bit type, many rows of X, and 64 full rows of X fit in LDS: the
 //           stripe is copied to LDS once and many block-rows are multiplied against it
 //   direct  everything else (operands straight from global memory)
-bsr_status launch_mfma(const spmm_args& a)
+bsr_status launch_mfma(const spmm_args& a, const tune_opts& tune)
 {
-    tune_opts t = read_tune_env();
+    tune_opts t = tune;
     int variant = t.variant;
     if (variant == 0) {
+        // thresholds from timed trials over many sizes (bsr_tune's candidates) on MI355X
         const int MM = a.W->bs_r >= 32 ? 32 : 16;
         const int64_t sub = (a.m + MM - 1) / MM;
-        if (sub * a.W->R < 4096 && a.W->mean_row_blocks > 1.5) variant = 2;
+        if (sub * a.W->R < 6000 && a.W->mean_row_blocks > 1.5) variant = 2;
         else if (a.W->bs_r >= 32 && a.m >= 512) variant = 3;
-        else if (a.m >= 256 && mfma_stripe_supports(a.W, 64)) variant = 4;
+        else if (a.m >= 256 && mfma_stripe_supports(a.W, 16)) variant = 4;
         else variant = 1;
-        if (variant == 3 && t.mt == 0) t.mt = 1;
+        if (variant == 3 && t.mt == 0) {
+            // fp32 blocks: 256-row tiles with one block in flight once m is large (the W block is
+            // staged half as often); otherwise 128-row tiles with two blocks in flight
+            const bool tall = a.W->dtype == BSR_F32 && a.m >= 2048;
+            t.mt = tall ? 2 : 1;
+            if (t.a == 0) t.a = tall ? 1 : 2;
+        }
     }
     if (variant == 2) return launch_mfma_ksplit(a, t);
     if (variant == 3) return launch_mfma_tile(a, t);

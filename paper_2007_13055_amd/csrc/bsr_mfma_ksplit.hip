@@ -237,13 +237,14 @@ bsr_status launch_ksplit_tile(const spmm_args& a, const tune_opts& tune)
     if ((int64_t)W->max_row_blocks * geo::BLK >= ((int64_t)1 << 31) || (int64_t)MM * k * geo::S >= ((int64_t)1 << 31))
         return BSR_ERR_UNSUPPORTED;
     // wavefronts per workgroup: about `per` stored blocks each for the longest block-row; at most 8
-    // when every workgroup has a CU to itself, at most 4 otherwise (starting wavefronts costs time
-    // too: about 11 cycles each per XCD), and no more than LDS has room for
+    // when every workgroup has a CU to itself, at most 4 up to four workgroups per CU and 2 beyond
+    // (starting wavefronts costs time too, about 11 cycles each per XCD, and with many workgroups the
+    // CUs are busy anyway), and no more than LDS has room for
     const int64_t tiles = (m + MM - 1) / MM;
     int64_t blocks = tiles * R;
     int per = tune.a > 0 ? tune.a : 2;
     int nw = (W->max_row_blocks + per - 1) / per;
-    const int nw_cap = blocks > 256 ? 4 : 8;
+    const int nw_cap = blocks > 1024 ? 2 : (blocks > 256 ? 4 : 8);
     nw = nw < 1 ? 1 : (nw > nw_cap ? nw_cap : nw);
     if (tune.nw >= 1 && tune.nw <= 8) nw = tune.nw;
     nw = std::min(nw, 160 * 1024 / geo::REGION);

@@ -234,7 +234,10 @@ bsr_status launch_stripe_types(const spmm_args& a, const tune_opts& tune)
                            n_groups, rows_per_group, (unsigned)(0x100000000ull / (unsigned)(k * sizeof(T) / 16)) + 1u);
         return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
     };
-    const int tm = tune.mt > 0 ? tune.mt * 16 : 64;
+    // rows of X per workgroup: the largest stripe that still leaves 32 m-tiles (fewer, taller stripes
+    // read W less often; too few leave CUs idle while a stripe is staged)
+    int tm = tune.mt > 0 ? tune.mt * 16 : (m >= 32 * 64 ? 64 : (m >= 32 * 32 ? 32 : 16));
+    while (tm > 16 && !mfma_stripe_supports(W, tm)) tm /= 2;      // wide X: a shorter stripe still fits LDS
     if (tm == 16) return go(std::integral_constant<int, 16>{});
     if (tm == 32) return go(std::integral_constant<int, 32>{});
     return go(std::integral_constant<int, 64>{});

@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256) void bsr_wave_generic(const T* __restrict__ X,
 }
 
 template <typename T, typename O>
-bsr_status launch_generic(const spmm_args& a)
+bsr_status launch_generic(const spmm_args& a, const tune_opts& tune)
 {
     const bsr_matrix* W = a.W;
     const int m = (int)a.m, n = (int)W->n, k = (int)W->k;
@@ -123,7 +123,6 @@ bsr_status launch_generic(const spmm_args& a)
     // 16-byte pieces when a block row is made of them (k is a multiple of bs_c and X, W are 16-byte
     // aligned, so every piece is aligned), single elements otherwise
     constexpr int V16 = 16 / (int)sizeof(T);
-    const tune_opts tune = read_tune_env();
     // rows of X per wavefront: 8 amortise the reads of W best when there are many rows; up to m = 8
     // the wavefronts are few and short, and 4 rows each (twice the wavefronts) finish sooner
     const int rows = tune.mt > 0 ? tune.mt : (m > 8 ? 8 : (m >= 4 ? 4 : m));
@@ -139,11 +138,11 @@ bsr_status launch_generic(const spmm_args& a)
 
 }  // namespace
 
-bsr_status launch_wave(const spmm_args& a)
+bsr_status launch_wave(const spmm_args& a, const tune_opts& t)
 {
     const bsr_dtype in = a.W->dtype, out = a.y_dtype;
-    if (in == BSR_F32) return launch_generic<float, float>(a);
-    if (in == BSR_F16) return out == BSR_F32 ? launch_generic<f16_t, float>(a) : launch_generic<f16_t, f16_t>(a);
-    if (in == BSR_BF16) return out == BSR_F32 ? launch_generic<bf16_t, float>(a) : launch_generic<bf16_t, bf16_t>(a);
+    if (in == BSR_F32) return launch_generic<float, float>(a, t);
+    if (in == BSR_F16) return out == BSR_F32 ? launch_generic<f16_t, float>(a, t) : launch_generic<f16_t, f16_t>(a, t);
+    if (in == BSR_BF16) return out == BSR_F32 ? launch_generic<bf16_t, float>(a, t) : launch_generic<bf16_t, bf16_t>(a, t);
     return BSR_ERR_DTYPE;
 }

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol(lib):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(bsr_[a-z_]+)\s*\(", header))
     assert {"bsr_validate", "bsr_workspace_size", "bsr_create", "bsr_destroy", "bsr_spmm", "bsr_spmm_ex",
-            "bsr_query_path", "bsr_status_string"} <= names
+            "bsr_query_path", "bsr_status_string", "bsr_tune", "bsr_scratch_size", "bsr_set_scratch"} <= names
     so = ctypes.CDLL(lib.library_path())
     for nme in names:
         assert hasattr(so, nme), nme
@@ -61,5 +61,6 @@ def test_status_strings(lib):
 def test_spmm_rejects_null_handle(lib):
     so = lib.load_library()
     assert so.bsr_spmm(None, 4, None, None, 0, None) == 1
+    assert so.bsr_tune(None, 4, None, None, 0, 5, None, None, None) == 1
     out = ctypes.c_int(0)
     assert so.bsr_query_path(None, 4, ctypes.byref(out)) == 1

@@ -372,3 +372,34 @@ def test_ksplit_work_item_table_and_m_changes(oracle_mod, monkeypatch):
         Yo, So = oracle_of(oracle_mod, p)
         Yg, W = gpu_product(p, path=MFMA, W=W)
         check(Yg, Yo, So, p.tau, f"k-split items m={m}")
+
+
+@pytest.mark.parametrize("case", [("f32", 32, 32, 128, 12, 12), ("bf16", 16, 16, 300, 20, 12), ("f16", 64, 64, 600, 6, 8),
+                                  ("f32", 16, 1, 100, 6, 90), ("f32", 8, 8, 8, 10, 16), ("f16", 16, 32, 40, 7, 9)])
+def test_tuned_product_matches_oracle(oracle_mod, case):
+    """bsr_tune runs every candidate kernel for the shape and remembers the fastest; the products after
+    it (whatever was chosen) meet the same bar, and Y right after tuning is already the product."""
+    import torch
+    import paper_2007_13055_amd as lib
+    dtype, bs_r, bs_c, m, R, C = case
+    rng = np.random.default_rng(m + R)
+    counts = rng.integers(0, C + 1, size=R)
+    counts[1] = 0
+    p = wl.make_problem("tune", m, C * bs_c, R * bs_r, bs_r, bs_c, dtype, dtype, ("counts", counts), ("normal", 1.0),
+                        ("normal", 1.0), 900 + m)
+    Yo, So = oracle_of(oracle_mod, p)
+    W = lib.bsr_create(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype=dtype)
+    X = to_device(p.X, dtype)
+    Y = torch.full((m, p.n), float("nan"), dtype=X.dtype, device="cuda")
+    tried, best_us = lib.bsr_tune(W, X, Y, trials=3)
+    assert tried >= 1 and best_us > 0
+    check(Y.double().cpu().numpy(), Yo, So, p.tau, f"tune {case}: Y after tuning", out_dtype=dtype)
+    Y2 = torch.full_like(Y, float("nan"))
+    lib.bsr_spmm(W, X, Y2)
+    torch.cuda.synchronize()
+    check(Y2.double().cpu().numpy(), Yo, So, p.tau, f"tune {case}: tuned product", out_dtype=dtype)
+    # another m on the same handle is untouched by what was remembered
+    Xs = X[: max(1, m // 2)].contiguous()
+    Ys = lib.bsr_spmm(W, Xs)
+    torch.cuda.synchronize()
+    check(Ys.double().cpu().numpy(), Yo[: Xs.shape[0]], So[: Xs.shape[0]], p.tau, f"tune {case}: other m", out_dtype=dtype)
