@@ -71,21 +71,38 @@ __global__ __launch_bounds__(256) void transpose_f32(const float* __restrict__ X
 //     serves four times faster than four 4-byte reads 64 bytes apart
 //   B operand (columns = the 16 outputs of the block-row): lane l supplies block_data[p + l/16][l%16]
 //   result of MFMA s: lane l holds tile rows 16*(l/16) + 4*j + s (j = 0..3), column l%16
-// A wavefront loads the block-columns and the blocks of U groups of 4 blocks, then issues all
-// 4*U gathers from XT before the first MFMA, so one memory latency covers up to 4*U blocks.
+// A wavefront works through its share in chunks of U groups of 4 blocks.  Per chunk it reads the
+// block-columns with one load (lane l takes block l of the chunk) and hands them to the lane groups
+// with ds_bpermute, reads the blocks themselves as contiguous 16-byte pieces into its own LDS area
+// and takes its B operands from there, then issues all U gathers from XT before the first MFMA, so
+// one memory latency covers up to 4*U blocks.  (Reading W and the block-columns one float per lane
+// cost 2*U load instructions per chunk, each occupying the memory pipeline for 16 cycles whatever
+// it carries: 3.4 of the kernel's 8.9 us.)  Blocks and block-columns are read through buffer
+// resources over the wavefront's share, so pieces past its end read as zero without branches.
 template <int U>
 __global__ __launch_bounds__(256) void bsr_thin16_f32(const float* __restrict__ XT, const float* __restrict__ data,
                                                       const int32_t* __restrict__ indices,
                                                       const int32_t* __restrict__ row_desc, float* __restrict__ Y,
-                                                      int m, int n, int R, int nnzb)
+                                                      int m, int n, int R, int mg)
 {
     constexpr int SUBS = 4;                           // 16-row MFMA tiles per wavefront: 64 rows
+    constexpr int WT = (U * 256 + 1023) / 1024;       // 1 KiB pieces of W per chunk (a block is 64 bytes)
     __shared__ float red[4][64][17];
+    __shared__ __attribute__((aligned(16))) unsigned char wstage[4][WT * 1024];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lo = lane & 15, pp = lane >> 4;
-    const int slot = (int)(blockIdx.x % (unsigned)R);
-    const int i0 = (int)(blockIdx.x / (unsigned)R) * 64;
+    // Workgroup -> (m-tile, slot).  The 8 XCDs take workgroups round-robin and have private L2s; XCD x
+    // works on the m-tiles t = x mod G (mod G) and the slots s = x div G (mod 8/G): it then gathers
+    // only from its own m-tiles' columns of XT -- with G = 8 every part of XT is fetched by one XCD
+    // only -- at the price of W being read by G XCDs (`mg` = G, a power of two up to 8).
+    const int x = (int)(blockIdx.x % 8u), j = (int)(blockIdx.x / 8u);
+    const int rg = 8 / mg;                            // slot groups
+    const int slots_here = (R - x / mg + rg - 1) / rg;   // slots of this XCD: x div G, x div G + 8/G, ...
+    const int ti = j / max(slots_here, 1), si = j - ti * max(slots_here, 1);
+    const int tile = x % mg + ti * mg, slot = x / mg + si * rg;
+    if (slots_here <= 0 || tile * 64 >= m) return;    // whole workgroup leaves together
+    const int i0 = tile * 64;
     const int32_t* __restrict__ desc = row_desc + (size_t)slot * kRowDescWords;
     const int r = desc[0];
     const int p0 = desc[1], nb = desc[2];
@@ -97,49 +114,39 @@ __global__ __launch_bounds__(256) void bsr_thin16_f32(const float* __restrict__ 
 #pragma unroll
     for (int s = 0; s < SUBS; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // Addressing is kept to "uniform base + per-lane 32-bit byte offset + immediate" so that a load
-    // costs at most one vector ALU instruction:
-    //   blocks / block-columns of group u: base(pb) + lane part + u*256 (resp. u*16) bytes
-    //   gather of group u:                 XT + (col*mp + i0 + 4*lo)*4 bytes, mp = m rounded up to 4
-    // The gather may read up to 63 floats past the m valid entries of an XT row (rows of X past m in
-    // the last tile): that lands in the next XT row, or in the scratch's tail padding for the last
-    // one; those rows of the result are never stored.
+    // The gather for group u reads XT + (col*mp + i0 + 4*lo)*4 bytes, mp = m rounded up to 4.  It may
+    // read up to 63 floats past the m valid entries of an XT row (rows of X past m in the last tile):
+    // that lands in the next XT row, or in the scratch's tail padding for the last one; those rows of
+    // the result are never stored.
     const unsigned char* xt_bytes = reinterpret_cast<const unsigned char*>(XT);
-    const unsigned char* w_bytes = reinterpret_cast<const unsigned char*>(data);
-    const unsigned char* i_bytes = reinterpret_cast<const unsigned char*>(indices);
-    const unsigned lane_w = (unsigned)(pp * 16 + lo) * 4u, lane_i = (unsigned)pp * 4u;
     const unsigned lane_x = (unsigned)(i0 + 4 * lo) * 4u;
+    const __amdgpu_buffer_rsrc_t wrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(data + (size_t)qb * 16), 0, (qe - qb) * 64, 0x00020000);
+    const __amdgpu_buffer_rsrc_t irsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(indices + qb), 0, (qe - qb) * 4, 0x00020000);
+    unsigned char* wl = wstage[wave];
 
     for (int pb = qb; pb < qe; pb += 4 * U) {
-        float wv[U];
+        const int rel = pb - qb;                      // first block of the chunk inside the share
+        const int idx = __builtin_amdgcn_raw_buffer_load_b32(irsrc, (rel + lane) * 4, 0, 0);   // 0 past the share
+        u32x4 w4[WT];
+#pragma unroll
+        for (int t = 0; t < WT; ++t) w4[t] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, rel * 64 + t * 1024 + lane * 16, 0, 0);
         int col[U];
-        if (pb + 4 * U <= nnzb) {                     // every block index of the chunk exists
-            const unsigned char* wb = w_bytes + (size_t)pb * 64;
-            const unsigned char* ib = i_bytes + (size_t)pb * 4;
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                wv[u] = *reinterpret_cast<const float*>(wb + lane_w + u * 256);
-                col[u] = *reinterpret_cast<const int32_t*>(ib + lane_i + u * 16);
-            }
-        } else {                                      // the last blocks of W: clamp each lane's block index
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int pc = min(pb + 4 * u + pp, qe - 1);
-                wv[u] = data[(size_t)pc * 16 + lo];
-                col[u] = indices[pc];
-            }
-        }
-        if (pb + 4 * U > qe) {                        // chunk reaches past this wavefront's share (uniform)
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (pb + 4 * u + pp >= qe) { wv[u] = 0.f; col[u] = 0; }   // contributes nothing
-        }
+        for (int u = 0; u < U; ++u) col[u] = __builtin_amdgcn_ds_bpermute((4 * u + pp) * 4, idx);
         f32x4 xv[U];
 #pragma unroll
         for (int u = 0; u < U; ++u)
             xv[u] = *reinterpret_cast<const f32x4*>(xt_bytes + ((unsigned)col[u] * row_bytes + lane_x));
-        // groups past the share multiply zeros (wv = 0, col = 0): no branch around the MFMAs, so the
-        // accumulators stay where they are
+        // the wavefront's own LDS area: its LDS operations complete in order, no barrier
+#pragma unroll
+        for (int t = 0; t < WT; ++t) *reinterpret_cast<u32x4*>(wl + t * 1024 + lane * 16) = w4[t];
+        float wv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) wv[u] = *reinterpret_cast<const float*>(wl + (4 * u + pp) * 64 + lo * 4);
+        // groups past the share multiply zeros (blocks read as zero, block-column 0): no branch around
+        // the MFMAs, so the accumulators stay where they are
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -185,11 +192,14 @@ bsr_status launch_mfma_thin(const spmm_args& a, const tune_opts& tune)
     if (hipGetLastError() != hipSuccess) return BSR_ERR_HIP;
     auto go = [&](auto u_tag) -> bsr_status {
         constexpr int U = decltype(u_tag)::value;
-        const int64_t blocks = (int64_t)((m + 63) / 64) * R;
+        // m-tile groups over the XCDs: as many as there are m-tiles, up to 8 (a power of two)
+        const int tiles = (m + 63) / 64;
+        const int mg = tune.b > 0 ? tune.b : (tiles >= 8 ? 8 : (tiles >= 4 ? 4 : (tiles >= 2 ? 2 : 1)));
+        const int64_t per_xcd = (int64_t)((tiles + mg - 1) / mg) * ((R + 8 / mg - 1) / (8 / mg));
+        const int64_t blocks = 8 * per_xcd;
         if (blocks >= ((int64_t)1 << 31)) return BSR_ERR_SHAPE;
         hipLaunchKernelGGL((bsr_thin16_f32<U>), dim3((unsigned)blocks), dim3(256), 0, a.stream,
-                           (const float*)XT, (const float*)W->data, W->indices, W->row_desc, (float*)a.Y, m, n, R,
-                           (int)W->nnzb);
+                           (const float*)XT, (const float*)W->data, W->indices, W->row_desc, (float*)a.Y, m, n, R, mg);
         return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
     };
     // groups of 4 blocks per chunk: a quarter of the longest block-row in one chunk when that is at

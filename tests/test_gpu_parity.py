@@ -319,13 +319,14 @@ def test_stripe_kernel_variant(oracle_mod, monkeypatch, extra, dtype, out):
         assert np.array_equal(Yg, Yg2), "two runs differ: race"
 
 
-@pytest.mark.parametrize("u", [0, 4, 8, 16])
+@pytest.mark.parametrize("u", ["", "a=4", "a=8", "a=16", "a=6,b=1", "a=10,b=2", "b=4", "a=14,b=8"])
 def test_thin_mfma_path(oracle_mod, monkeypatch, u):
-    """16x1 fp32 blocks on the matrix-core path: transposed copy of X in lent scratch, then gather + MFMA."""
+    """16x1 fp32 blocks on the matrix-core path: transposed copy of X in lent scratch, then gather + MFMA
+    (a = groups of 4 blocks per chunk, b = m-tile groups over the XCDs)."""
     import paper_2007_13055_amd as lib
     if u:
-        monkeypatch.setenv("BSR_SPMM_TUNE", f"a={u}")
-    for m, R, C in ((32, 3, 40), (70, 9, 130), (257, 20, 300), (64, 5, 7)):
+        monkeypatch.setenv("BSR_SPMM_TUNE", u)
+    for m, R, C in ((32, 3, 40), (70, 9, 130), (257, 20, 300), (64, 5, 7), (600, 11, 64)):
         rng = np.random.default_rng(m + R)
         counts = rng.integers(0, min(C, 90) + 1, size=R)
         counts[0] = 0
