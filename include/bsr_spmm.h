@@ -107,7 +107,8 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
                       const int32_t* block_indices_host, const int32_t* index_pointer_host,
                       void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
-/* Frees the handle's host memory only.  NULL is accepted. */
+/* Frees the handle's host memory only (after waiting for a plan upload that may still read it).
+ * NULL is accepted. */
 void bsr_destroy(bsr_matrix* W);
 
 /*
@@ -116,8 +117,11 @@ void bsr_destroy(bsr_matrix* W);
  *   y_dtype W's dtype or BSR_F32; the fp32 accumulator is rounded to nearest-even on store
  *   m       any value >= 0 (m == 0 returns BSR_OK without device work)
  * Every element of Y is written; columns of an empty block-row are exact zeros.  Asynchronous on
- * `hip_stream`; no hidden synchronisation; safe to call concurrently on one handle unless the
- * product uses lent scratch (see bsr_set_scratch).
+ * `hip_stream`; no hidden synchronisation (a call with a new m may wait for the host side of the
+ * previous m's work-list upload).  Products with the same m may run concurrently on one
+ * handle (unless they use lent scratch, see bsr_set_scratch); products with different m share a
+ * per-m work list in the workspace, uploaded on the call's stream, so keep them ordered on one
+ * stream.
  * Errors: NULL, SHAPE (m < 0 or m*max(k,n) >= 2^31), DTYPE, ALIGN, HIP.
  */
 bsr_status bsr_spmm(const bsr_matrix* W, int64_t m, const void* X_dev, void* Y_dev,

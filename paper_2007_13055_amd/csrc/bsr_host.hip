@@ -110,6 +110,10 @@ int ksplit_items(const bsr_matrix* W, int tiles, hipStream_t stream)
     const size_t grid = levels * (size_t)n_cu;
     if (grid == 0 || grid > W->item_capacity) return 0;
     const int32_t* base = W->staging.data() + (W->row_desc - W->row_order);   // host copy of the row descriptors
+    // the previous table's upload may still be reading item_host: wait for it before rewriting the
+    // buffer (an event that was only captured into a graph cannot be waited for; its upload ran at
+    // capture's warm-up or will read the buffer at replay, which a caller changing m must order itself)
+    if (W->item_uploaded) (void)hipEventSynchronize(W->item_uploaded);
     W->item_host.assign(grid * kRowDescWords, 0);
     for (size_t b = 0; b < grid; ++b) {
         int32_t* d = W->item_host.data() + b * kRowDescWords;
@@ -123,6 +127,10 @@ int ksplit_items(const bsr_matrix* W, int tiles, hipStream_t stream)
     if (hipMemcpyAsync(W->item_desc, W->item_host.data(), W->item_host.size() * sizeof(int32_t),
                        hipMemcpyHostToDevice, stream) != hipSuccess)
         return 0;
+    if (!W->item_uploaded && hipEventCreateWithFlags(&W->item_uploaded, hipEventDisableTiming) != hipSuccess)
+        W->item_uploaded = nullptr;
+    if (W->item_uploaded) (void)hipEventRecord(W->item_uploaded, stream);
+    (void)hipGetLastError();                          // a refused record (stream capture) is not an error of the product
     W->item_tiles = tiles;
     W->item_grid = (int)grid;
     W->item_cus = n_cu;
@@ -270,12 +278,27 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
         hipError_t e = hipMemcpyAsync(workspace_dev, W->staging.data(), sizeof(int32_t) * words,
                                       hipMemcpyHostToDevice, (hipStream_t)hip_stream);
         if (e != hipSuccess) { delete W; return BSR_ERR_HIP; }
+        if (hipEventCreateWithFlags(&W->plan_uploaded, hipEventDisableTiming) == hipSuccess)
+            (void)hipEventRecord(W->plan_uploaded, (hipStream_t)hip_stream);
+        else
+            W->plan_uploaded = nullptr;
+        (void)hipGetLastError();
     }
     *out = W;
     return BSR_OK;
 }
 
-void bsr_destroy(bsr_matrix* W) { delete W; }
+void bsr_destroy(bsr_matrix* W)
+{
+    if (!W) return;
+    for (hipEvent_t e : {W->plan_uploaded, W->item_uploaded}) {   // uploads read the handle's host buffers
+        if (!e) continue;
+        (void)hipEventSynchronize(e);
+        (void)hipEventDestroy(e);
+        (void)hipGetLastError();
+    }
+    delete W;
+}
 
 bsr_status bsr_query_path(const bsr_matrix* W, int64_t m, bsr_path* path_out)
 {

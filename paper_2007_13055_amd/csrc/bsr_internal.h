@@ -67,11 +67,13 @@ struct bsr_matrix {
     mutable int item_grid = 0;               // workgroups of the cached table
     mutable int item_cus = 0;                // CUs the cached table was laid out for (entry b runs on CU b mod item_cus)
     mutable std::vector<int32_t> item_host;  // host copy (kept alive for the asynchronous upload)
+    mutable hipEvent_t item_uploaded = nullptr;   // recorded behind the upload: waited for before item_host changes
     int32_t max_row_blocks = 0;              // longest block-row
     int32_t long_rows = 0;                   // leading slots whose block count is > 4x the mean and > 8 ("long" bin)
     int32_t empty_rows = 0;                  // block-rows with no stored block
     double mean_row_blocks = 0.0;
     std::vector<int32_t> staging;            // host copy of what was uploaded (kept for the async copy)
+    hipEvent_t plan_uploaded = nullptr;      // recorded behind that copy: bsr_destroy waits for it
     // Optional per-call scratch lent by the caller (bsr_set_scratch): device memory some kernels
     // need beyond X, W and Y (the thin-block path keeps a transposed copy of X there).
     void* scratch = nullptr;
