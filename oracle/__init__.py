@@ -53,6 +53,8 @@ def _load():
         lib.oracle_bsr_spmm_rows.argtypes = [i64, i64, i64, i32, i32, i64, vp, vp, vp, vp,
                                              i64, vp, vp, vp]
         lib.oracle_bsr_spmm_rows.restype = ctypes.c_int
+        lib.oracle_bsr_spmm_w.argtypes = [i64, i64, i64, i32, i32, i64, vp, vp, vp, vp, vp, vp]
+        lib.oracle_bsr_spmm_w.restype = ctypes.c_int
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -120,3 +122,29 @@ def bsr_spmm(X, block_data, block_indices, index_pointer, n, rows=None):
     if st != 0:
         raise ValueError("oracle: " + _STATUS.get(st, f"status {st}"))
     return Y, S
+
+
+def bsr_spmm_w(G, block_data, block_indices, index_pointer, k):
+    """Return (Z, S) as float64 arrays for the sibling product Z = G * W (G (m, n), W (n, k) in BSR):
+    the gradient of the layer's input.  Arguments as for bsr_spmm; k = columns of W (= columns of Z)."""
+    G = _as_f32(G, "G")
+    if G.ndim != 2:
+        raise ValueError("G must be 2-D")
+    m, n = G.shape
+    block_data = _as_f32(block_data, "block_data")
+    if block_data.ndim != 3:
+        raise ValueError("block_data must be (nnzb, b_r, b_c)")
+    nnzb, b_r, b_c = block_data.shape
+    idx = np.ascontiguousarray(np.asarray(block_indices, dtype=np.int32).reshape(-1))
+    ptr = np.ascontiguousarray(np.asarray(index_pointer, dtype=np.int32).reshape(-1))
+    if idx.shape[0] != nnzb:
+        raise ValueError("block_indices length differs from the number of stored blocks")
+    if b_r <= 0 or b_c <= 0 or n % b_r != 0 or ptr.shape[0] != n // b_r + 1:
+        raise ValueError("index_pointer must have n / b_r + 1 entries with b_r | n")
+    Z = np.empty((m, k), dtype=np.float64)
+    S = np.empty((m, k), dtype=np.float64)
+    st = _load().oracle_bsr_spmm_w(m, k, n, b_r, b_c, nnzb, G.ctypes.data, block_data.ctypes.data,
+                                   idx.ctypes.data, ptr.ctypes.data, Z.ctypes.data, S.ctypes.data)
+    if st != 0:
+        raise ValueError("oracle: " + _STATUS.get(st, f"status {st}"))
+    return Z, S

@@ -147,3 +147,58 @@ int oracle_bsr_spmm(int64_t m, int64_t k, int64_t n, int32_t b_r, int32_t b_c, i
     return oracle_bsr_spmm_rows(m, k, n, b_r, b_c, nnzb, X, block_data, block_indices,
                                 index_pointer, m, NULL, Y, S);
 }
+
+/*
+ * The sibling product  Z = G * W  (G dense (m, n), same BSR arrays of W; Z is (m, k)).
+ *
+ * The paper gives Y = X W_B^T for the forward pass of a sparse fully connected layer and names
+ * training as the use (Introduction); the gradient with respect to X of any function of Y is
+ * (dL/dY) W, i.e. this product with G = dL/dY.  Written out from the same storage definition:
+ *
+ *   Z[i][block_indices[p]*b_c + c] = sum over block-rows r, over the stored blocks p of r, over
+ *                                    a in [0, b_r) of  G[i][r*b_r + a] * block_data[p][a][c]
+ *
+ * Columns of Z whose block-column holds no stored block are exact zeros.  S is the same sum over
+ * absolute values.  Order: r ascending, p ascending, a ascending (a plain scatter into Z, one row
+ * of G at a time); double throughout.
+ */
+int oracle_bsr_spmm_w(int64_t m, int64_t k, int64_t n, int32_t b_r, int32_t b_c, int64_t nnzb,
+                      const float* G, const float* block_data,
+                      const int32_t* block_indices, const int32_t* index_pointer,
+                      double* Z, double* S)
+{
+    if (m < 0) return ORACLE_BAD_ARGUMENT;
+    int st = check_structure(k, n, b_r, b_c, nnzb, block_indices, index_pointer);
+    if (st != ORACLE_OK) return st;
+    if (m == 0 || k == 0) return ORACLE_OK;
+    if (!Z || (n > 0 && !G) || (nnzb > 0 && !block_data)) return ORACLE_BAD_ARGUMENT;
+
+    const int64_t R = n / b_r;
+    const int64_t block_elems = (int64_t)b_r * b_c;
+
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < m; ++i) {
+        double* z_row = Z + i * k;
+        double* s_row = S ? S + i * k : NULL;
+        for (int64_t j = 0; j < k; ++j) {
+            z_row[j] = 0.0;
+            if (s_row) s_row[j] = 0.0;
+        }
+        const float* g_row = G + i * n;
+        for (int64_t r = 0; r < R; ++r) {
+            for (int64_t p = index_pointer[r]; p < index_pointer[r + 1]; ++p) {
+                const int64_t col0 = (int64_t)block_indices[p] * b_c;
+                for (int32_t a = 0; a < b_r; ++a) {
+                    const double g = (double)g_row[r * b_r + a];
+                    const float* w_row = block_data + p * block_elems + (int64_t)a * b_c;
+                    for (int32_t c = 0; c < b_c; ++c) {
+                        const double prod = g * (double)w_row[c];
+                        z_row[col0 + c] += prod;
+                        if (s_row) s_row[col0 + c] += fabs(prod);
+                    }
+                }
+            }
+        }
+    }
+    return ORACLE_OK;
+}

@@ -273,3 +273,55 @@ def test_empty_inputs(oracle_mod):
     Y, S = oracle_mod.bsr_spmm(np.ones((3, 8), np.float32), np.zeros((0, 4, 4), np.float32),
                                [], [0, 0, 0], 8)
     assert Y.shape == (3, 8) and np.all(Y == 0) and np.all(S == 0)
+
+
+# ---------------------------------------------------------------- the sibling product Z = G W
+def run_w(oracle_mod, p, G):
+    return oracle_mod.bsr_spmm_w(G, p.block_data, p.block_indices, p.index_pointer, p.k)
+
+
+def test_sibling_hand_worked_fixture(oracle_mod):
+    """Z = G W on the hand-worked 4x4 example.  Catches: a/c swapped, scatter to the wrong block-column."""
+    with open(os.path.join(GOLDEN, "hand_worked_2x2.json")) as f:
+        g = json.load(f)
+    Z, S = oracle_mod.bsr_spmm_w(np.array(g["G"], dtype=np.float32), np.array(g["block_data"], dtype=np.float32),
+                                 g["block_indices"], g["index_pointer"], g["k"])
+    assert np.array_equal(Z, np.array(g["Z"], dtype=np.float64))
+    assert np.array_equal(S, np.array(g["S_Z"], dtype=np.float64))
+
+
+@pytest.mark.parametrize("shape", [(5, 24, 18, 3, 4, 0.4), (3, 32, 48, 16, 16, 0.3), (7, 40, 64, 16, 1, 0.2), (1, 8, 8, 1, 1, 0.5)])
+def test_sibling_matches_dense_gemm_and_scipy(oracle_mod, shape):
+    """Z against numpy's G @ Wd with W expanded to dense, and against SciPy's BSR type built from the
+    same three arrays.  Catches every indexing mistake of the scatter."""
+    m, k, n, bs_r, bs_c, d = shape
+    p = rand_problem(31 + m, m, k, n, bs_r, bs_c, d)
+    G = np.random.default_rng(m).normal(size=(m, n)).astype(np.float32)
+    Z, S = run_w(oracle_mod, p, G)
+    Wd = dense_expand(p.block_data, p.block_indices, p.index_pointer, n, k)
+    assert np.all(np.abs(Z - G.astype(np.float64) @ Wd) <= 1e-12 * (S + 1e-300))
+    assert np.all(np.abs(S - np.abs(G.astype(np.float64)) @ np.abs(Wd)) <= 1e-12 * (S + 1e-300))
+    Wsp = sp.bsr_matrix((p.block_data.astype(np.float64), p.block_indices, p.index_pointer), shape=(n, k))
+    assert np.all(np.abs(Z - (Wsp.T @ G.astype(np.float64).T).T) <= 1e-12 * (S + 1e-300))
+
+
+def test_sibling_is_the_adjoint_of_the_forward_product(oracle_mod):
+    """<X W^T, G> = <X, G W> for any X, G: ties the two oracle functions to each other through the
+    mathematics (not through shared code paths: one gathers, the other scatters)."""
+    p = rand_problem(77, 6, 48, 40, 8, 16, 0.35)
+    G = np.random.default_rng(5).normal(size=(p.m, p.n)).astype(np.float32)
+    Y, _ = run(oracle_mod, p)
+    Z, _ = run_w(oracle_mod, p, G)
+    lhs, rhs = float(np.sum(Y * G)), float(np.sum(p.X.astype(np.float64) * Z))
+    assert abs(lhs - rhs) <= 1e-10 * (abs(lhs) + 1.0)
+
+
+def test_sibling_empty_block_columns_are_exact_zero(oracle_mod):
+    """A block-column without a stored block gives exact zeros in Z (and S)."""
+    rng = np.random.default_rng(9)
+    ptr, idx = wl.pattern_from_mask(np.array([[1, 0, 1, 0], [0, 0, 1, 0], [1, 0, 0, 0]], dtype=bool))
+    data = rng.normal(size=(idx.shape[0], 4, 2)).astype(np.float32)
+    G = rng.normal(size=(5, 12)).astype(np.float32)
+    Z, S = oracle_mod.bsr_spmm_w(G, data, idx, ptr, 8)
+    assert np.all(Z[:, 2:4] == 0) and np.all(Z[:, 6:8] == 0) and np.all(S[:, 2:4] == 0)
+    assert np.all(S[:, 0:2] > 0)
