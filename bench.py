@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of bsr_spmm on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-all-configs] [--no-cpu] [--paper-grid] [--peaks]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-all-configs] [--no-cpu] [--paper-grid] [--sibling] [--peaks]
 
 A step is one whole product Y = X * W^T (one bsr_spmm call) on the headline workload, the
 "Transformer FFN weight" configuration (fp32, m=128, k=n=3072, 32x32 blocks, density 0.10), with
@@ -170,6 +170,32 @@ def _paper_grid(steps, chunk):
     return rows
 
 
+def _sibling(p, steps, chunk):
+    """The sibling product Z = G * W (gradient of the layer's input) on workload p: the same kernels on
+    the handle of W^T; also the time of re-transposing the block values on the device (needed once
+    per update of W)."""
+    import torch
+    import numpy as np
+    import paper_2007_13055_amd as lib
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+    WT = lib.bsr_create_transposed(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype=p.in_dtype)
+    G = torch.randn((p.m, p.n), device="cuda").to(tdt[p.in_dtype])
+    Z = torch.empty((p.m, p.k), dtype=tdt[p.out_dtype], device="cuda")
+    _, ev, mode = _time_steps(lambda: lib.bsr_spmm(WT, G, Z), steps, 20, chunk)
+    _, _, perm = lib.bsr_transpose_pattern(p.n, p.k, p.bs_r, p.bs_c, p.index_pointer, p.block_indices)
+    perm_dev = torch.from_numpy(perm).to("cuda")
+    src = torch.from_numpy(np.ascontiguousarray(p.block_data, dtype=np.float32)).to("cuda", dtype=tdt[p.in_dtype])
+    dst = torch.empty((p.nnzb, p.bs_c, p.bs_r), dtype=src.dtype, device="cuda")
+    so, code = lib.load_library(), {"f32": 0, "f16": 1, "bf16": 2}[p.in_dtype]
+    stream = lambda: torch.cuda.current_stream().cuda_stream
+    tr = lambda: so.bsr_transpose_values(code, p.bs_r, p.bs_c, p.nnzb, perm_dev.data_ptr(), src.data_ptr(),
+                                         dst.data_ptr(), stream())
+    _, ev_t, _ = _time_steps(tr, steps, 20, chunk)
+    s = ev / steps
+    return {"us_per_product": s * 1e6, "tflops": p.flops / s / 1e12, "launch": mode,
+            "transpose_values_us": ev_t / steps * 1e6}
+
+
 def _measured_peaks():
     """What this machine delivers on plain library work, for context beside the published peaks the roofline
     uses: a 1 GiB device-to-device copy (read + written bytes per second) and large dense GEMMs through
@@ -212,6 +238,8 @@ def main():
                     help="launches per captured HIP graph (0 = plain launches only)")
     ap.add_argument("--no-all-configs", action="store_true", help="skip the per-configuration table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--sibling", action="store_true",
+                    help="also time the sibling product Z = G * W (through the handle of W^T) on the headline workload")
     ap.add_argument("--peaks", action="store_true",
                     help="also time a 1 GiB copy and two large torch GEMMs on this box and add them as 'measured_peaks'")
     ap.add_argument("--paper-grid", action="store_true",
@@ -279,6 +307,8 @@ def main():
         out["per_config"] = table
     if a.paper_grid:
         out["paper_grid"] = _paper_grid(a.steps, chunk)
+    if a.sibling:
+        out["sibling"] = _sibling(p, a.steps, chunk)
     if a.peaks:
         out["measured_peaks"] = _measured_peaks()
     print(json.dumps(out))

@@ -181,6 +181,30 @@ bsr_status bsr_tune_result(const bsr_matrix* W, int64_t m, bsr_dtype y_dtype, in
  * remembered is not consulted).  Errors: NULL. */
 bsr_status bsr_query_path(const bsr_matrix* W, int64_t m, bsr_path* path_out);
 
+/*
+ * The sibling product Z = G * W (the gradient of the layer's input when Y = X * W^T is a sparse
+ * layer's forward pass, the use the paper's Introduction names) is the same product with W^T in
+ * place of W:  Z = G * (W^T)^T.  These two calls build W^T in the same storage format -- a (k, n)
+ * matrix of bs_c x bs_r blocks -- from which bsr_create() makes a handle; then
+ * bsr_spmm(handle of W^T, m, G, Z, ...) is the sibling product.
+ *
+ * bsr_transpose_pattern (HOST pointers): validates the pattern as bsr_validate and writes
+ *   t_index_pointer_host  k/bs_c + 1 entries      t_block_indices_host  nnzb entries (block-rows of W)
+ *   perm_host             nnzb entries: stored block q of W^T is the transpose of block perm[q] of W
+ * The blocks of a block-row of W^T come by ascending block-row of W.
+ *
+ * bsr_transpose_values (DEVICE pointers, asynchronous on hip_stream):
+ *   t_block_data[q][c][a] = block_data[perm[q]][a][c],  q in [0, nnzb)
+ * t_block_data_dev has nnzb*bs_c*bs_r elements of `dtype`, caller-owned; call it again whenever
+ * the values of W change.  Errors: NULL, SHAPE, DTYPE, INDPTR, INDEX, UNSUPPORTED (a block larger
+ * than 64 KiB), HIP.
+ */
+bsr_status bsr_transpose_pattern(int64_t n, int64_t k, int32_t bs_r, int32_t bs_c, int64_t nnzb,
+                                 const int32_t* index_pointer_host, const int32_t* block_indices_host,
+                                 int32_t* t_index_pointer_host, int32_t* t_block_indices_host, int32_t* perm_host);
+bsr_status bsr_transpose_values(bsr_dtype dtype, int32_t bs_r, int32_t bs_c, int64_t nnzb, const int32_t* perm_dev,
+                                const void* block_data_dev, void* t_block_data_dev, void* hip_stream);
+
 /* Static, human-readable text for a status code. */
 const char* bsr_status_string(bsr_status s);
 

@@ -52,6 +52,8 @@ def load_library():
     lib.bsr_tune_result.argtypes = [vp, i64, ctypes.c_int, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float)]
     lib.bsr_scratch_size.argtypes = [vp, i64, ctypes.POINTER(sz)]
     lib.bsr_set_scratch.argtypes = [vp, vp, sz]
+    lib.bsr_transpose_pattern.argtypes = [i64, i64, i32, i32, i64, vp, vp, vp, vp, vp]
+    lib.bsr_transpose_values.argtypes = [ctypes.c_int, i32, i32, i64, vp, vp, vp, vp]
     lib.bsr_status_string.argtypes = [ctypes.c_int]
     lib.bsr_status_string.restype = ctypes.c_char_p
     for f in ("bsr_validate", "bsr_workspace_size", "bsr_create", "bsr_spmm", "bsr_spmm_ex", "bsr_query_path",
@@ -167,6 +169,47 @@ def bsr_create(n, k, block_data, block_indices, index_pointer, dtype=None, devic
     if st != 0:
         raise BsrError(st, "bsr_create")
     return BsrMatrix(handle, n, k, bs_r, bs_c, dtype, (data_dev, idx_dev, ptr_dev, ws))
+
+
+def bsr_transpose_pattern(n, k, bs_r, bs_c, index_pointer, block_indices):
+    """Pattern of W^T: (t_index_pointer, t_block_indices, perm) as int32 numpy arrays."""
+    ptr, idx = _i32(index_pointer), _i32(block_indices)
+    nnzb = int(idx.shape[0])
+    if bs_c <= 0 or k % bs_c:
+        raise BsrError(2, "bsr_transpose_pattern")
+    t_ptr = np.zeros(k // bs_c + 1, dtype=np.int32)
+    t_idx = np.zeros(max(nnzb, 1), dtype=np.int32)
+    perm = np.zeros(max(nnzb, 1), dtype=np.int32)
+    st = load_library().bsr_transpose_pattern(n, k, bs_r, bs_c, nnzb, ptr.ctypes.data, idx.ctypes.data if nnzb else None,
+                                              t_ptr.ctypes.data, t_idx.ctypes.data, perm.ctypes.data)
+    if st != 0:
+        raise BsrError(st, "bsr_transpose_pattern")
+    return t_ptr, t_idx[:nnzb], perm[:nnzb]
+
+
+def bsr_create_transposed(n, k, block_data, block_indices, index_pointer, dtype=None, device="cuda") -> BsrMatrix:
+    """Handle of W^T (k x n, blocks bs_c x bs_r) for the sibling product Z = G * W = bsr_spmm(W^T, G).
+    Arguments as bsr_create (they describe W); the transposed values are computed on the device."""
+    import torch
+    if isinstance(block_data, torch.Tensor):
+        dtype = dtype or _dtype_name(block_data)
+        data_dev = block_data.to(device=device, dtype=_torch_dtype(dtype)).contiguous()
+    else:
+        dtype = dtype or "f32"
+        data_dev = torch.from_numpy(np.ascontiguousarray(block_data, dtype=np.float32)).to(
+            device=device, dtype=_torch_dtype(dtype)).contiguous()
+    nnzb, bs_r, bs_c = (int(v) for v in data_dev.shape)
+    t_ptr, t_idx, perm = bsr_transpose_pattern(n, k, bs_r, bs_c, index_pointer, block_indices)
+    t_data = torch.empty((nnzb, bs_c, bs_r), dtype=data_dev.dtype, device=device)
+    if nnzb:
+        perm_dev = torch.from_numpy(perm).to(device)
+        st = load_library().bsr_transpose_values(_DTYPE_CODE[dtype], bs_r, bs_c, nnzb, perm_dev.data_ptr(),
+                                                 data_dev.data_ptr(), t_data.data_ptr(),
+                                                 torch.cuda.current_stream().cuda_stream)
+        if st != 0:
+            raise BsrError(st, "bsr_transpose_values")
+        torch.cuda.current_stream().synchronize()     # perm_dev and data_dev may be freed on return
+    return bsr_create(k, n, t_data, t_idx, t_ptr, dtype=dtype, device=device)
 
 
 def bsr_spmm_ex(W: BsrMatrix, X, Y=None, y_dtype=None, path=PATH_AUTO):

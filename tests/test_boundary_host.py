@@ -64,3 +64,29 @@ def test_spmm_rejects_null_handle(lib):
     assert so.bsr_tune(None, 4, None, None, 0, 5, None, None, None) == 1
     out = ctypes.c_int(0)
     assert so.bsr_query_path(None, 4, ctypes.byref(out)) == 1
+
+
+def test_transpose_pattern_against_scipy(lib):
+    """bsr_transpose_pattern: the pattern of W^T equals what SciPy's CSR transpose gives for the same
+    block pattern; perm maps every block of W^T to its source; blocks of a block-row of W^T come by
+    ascending block-row of W; duplicates survive."""
+    import numpy as np
+    import scipy.sparse as sp
+    rng = np.random.default_rng(4)
+    R, C = 9, 7
+    mask = rng.random((R, C)) < 0.4
+    mask[3, :] = False
+    mask[:, 2] = False
+    ptr = np.concatenate([[0], np.cumsum(mask.sum(1))]).astype(np.int32)
+    idx = np.concatenate([np.nonzero(row)[0] for row in mask]).astype(np.int32)
+    t_ptr, t_idx, perm = lib.bsr_transpose_pattern(R * 4, C * 8, 4, 8, ptr, idx)
+    ref = sp.csr_matrix((np.arange(1, idx.shape[0] + 1), idx, ptr), shape=(R, C)).T.tocsr()
+    ref.sort_indices()
+    assert np.array_equal(t_ptr, ref.indptr) and np.array_equal(t_idx, ref.indices)
+    assert np.array_equal(perm, ref.data - 1)
+    # duplicates and unsorted columns: every block appears exactly once, order inside a row of W^T stable
+    ptr2, idx2 = np.array([0, 3, 4], np.int32), np.array([1, 0, 1, 1], np.int32)
+    t_ptr2, t_idx2, perm2 = lib.bsr_transpose_pattern(2, 2, 1, 1, ptr2, idx2)
+    assert t_ptr2.tolist() == [0, 1, 4] and t_idx2.tolist() == [0, 0, 0, 1] and perm2.tolist() == [1, 0, 2, 3]
+    with pytest.raises(lib.BsrError):
+        lib.bsr_transpose_pattern(8, 8, 4, 4, [0, 1, 1], [5])          # column out of range

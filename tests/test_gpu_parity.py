@@ -404,3 +404,30 @@ def test_tuned_product_matches_oracle(oracle_mod, case):
     Ys = lib.bsr_spmm(W, Xs)
     torch.cuda.synchronize()
     check(Ys.double().cpu().numpy(), Yo[: Xs.shape[0]], So[: Xs.shape[0]], p.tau, f"tune {case}: other m", out_dtype=dtype)
+
+
+@pytest.mark.parametrize("case", [("f32", 32, 32, 128, 10, 12), ("bf16", 16, 16, 300, 20, 12), ("f16", 64, 32, 70, 5, 9),
+                                  ("f32", 16, 1, 40, 6, 50), ("f32", 8, 4, 8, 10, 16), ("f16", 16, 64, 1, 7, 3)])
+def test_sibling_product_through_transposed_handle(oracle_mod, case):
+    """Z = G * W as bsr_spmm on the handle of W^T (bsr_transpose_pattern + bsr_transpose_values), against
+    the oracle's own sibling product; and the transposed values are exactly W's, block by block."""
+    import torch
+    import paper_2007_13055_amd as lib
+    dtype, bs_r, bs_c, m, R, C = case
+    rng = np.random.default_rng(m + R + C)
+    counts = rng.integers(0, C + 1, size=R)
+    counts[0] = 0
+    p = wl.make_problem("sib", m, C * bs_c, R * bs_r, bs_r, bs_c, dtype, dtype, ("counts", counts), ("normal", 1.0),
+                        ("normal", 1.0), 950 + m)
+    G = wl.round_to_storage(rng.normal(size=(m, p.n)).astype(np.float32), dtype)
+    Zo, So = oracle_mod.bsr_spmm_w(G, p.block_data, p.block_indices, p.index_pointer, p.k)
+    WT = lib.bsr_create_transposed(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype=dtype)
+    assert (WT.n, WT.k, WT.bs_r, WT.bs_c) == (p.k, p.n, bs_c, bs_r)
+    t_ptr, t_idx, perm = lib.bsr_transpose_pattern(p.n, p.k, bs_r, bs_c, p.index_pointer, p.block_indices)
+    got = WT.block_data.float().cpu().numpy()
+    assert np.array_equal(got, np.transpose(p.block_data[perm], (0, 2, 1)))
+    Gd = to_device(G, dtype)
+    Z = torch.full((m, p.k), float("nan"), dtype=Gd.dtype, device="cuda")
+    lib.bsr_spmm(WT, Gd, Z)
+    torch.cuda.synchronize()
+    check(Z.double().cpu().numpy(), Zo, So, p.tau, f"sibling {case}", out_dtype=dtype)
