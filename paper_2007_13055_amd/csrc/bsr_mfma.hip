@@ -163,7 +163,8 @@ bool mfma_supports(const bsr_matrix* W)
 //           the X tile staged in LDS with coalesced reads, XCD-aware launch order
 //   stripe  16x16 blocks of a 16-bit type, many rows of X, and 64 full rows of X fit in LDS: the
 //           stripe is copied to LDS once and many block-rows are multiplied against it
-//   direct  everything else (operands straight from global memory)
+//   direct  everything else: block-rows of a block or two, where writing Y is most of the work
+//           (operands straight from global memory)
 bsr_status launch_mfma(const spmm_args& a, const tune_opts& tune)
 {
     tune_opts t = tune;
@@ -175,6 +176,7 @@ bsr_status launch_mfma(const spmm_args& a, const tune_opts& tune)
         if (sub * a.W->R < 6000 && a.W->mean_row_blocks > 1.5) variant = 2;
         else if (a.W->bs_r >= 32 && a.m >= 512) variant = 3;
         else if (a.m >= 256 && mfma_stripe_supports(a.W, 16)) variant = 4;
+        else if (a.W->mean_row_blocks > 4.0) variant = 2;     // 16-row blocks the tile kernel does not take
         else variant = 1;
         if (variant == 3 && t.mt == 0) {
             // fp32 blocks: 256-row tiles with one block in flight once m is large (the W block is
