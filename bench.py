@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of bsr_spmm on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-all-configs] [--no-cpu] [--paper-grid] [--sibling] [--peaks]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-all-configs] [--no-cpu] [--paper-grid] [--cold] [--sibling] [--peaks]
 
 A step is one whole product Y = X * W^T (one bsr_spmm call) on the headline workload, the
 "Transformer FFN weight" configuration (fp32, m=128, k=n=3072, 32x32 blocks, density 0.10), with
@@ -196,6 +196,30 @@ def _sibling(p, steps, chunk):
             "transpose_values_us": ev_t / steps * 1e6}
 
 
+def _cold(p, steps):
+    """The headline product with operands that are NOT resident in the 256 MB last-level cache: the calls
+    rotate through enough distinct (X, Y) pairs (and copies of W's values) that 1 GiB of other data
+    passes between two uses of the same buffer.  Plain launches (a graph would pin one buffer set)."""
+    import torch
+    import paper_2007_13055_amd as lib
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+    per_set = p.algorithmic_bytes()
+    sets = max(2, min(512, int((1 << 30) // max(per_set, 1)) + 1))
+    Ws, Xs, Ys = [], [], []
+    for _ in range(sets):
+        W, X, Y = _upload(p)
+        Ws.append(W); Xs.append(X); Ys.append(Y)
+    state = {"i": 0}
+
+    def fn():
+        i = state["i"] = (state["i"] + 1) % sets
+        lib.bsr_spmm(Ws[i], Xs[i], Ys[i])
+    _, ev, _ = _time_steps(fn, steps, sets, 0)
+    s = ev / steps
+    return {"us_per_product": s * 1e6, "tflops": p.flops / s / 1e12, "buffer_sets": sets,
+            "hbm_GBs_algorithmic": per_set / s / 1e9, "launch": "eager"}
+
+
 def _measured_peaks():
     """What this machine delivers on plain library work, for context beside the published peaks the roofline
     uses: a 1 GiB device-to-device copy (read + written bytes per second) and large dense GEMMs through
@@ -238,6 +262,8 @@ def main():
                     help="launches per captured HIP graph (0 = plain launches only)")
     ap.add_argument("--no-all-configs", action="store_true", help="skip the per-configuration table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--cold", action="store_true",
+                    help="also time the headline product on operands rotated out of the last-level cache")
     ap.add_argument("--sibling", action="store_true",
                     help="also time the sibling product Z = G * W (through the handle of W^T) on the headline workload")
     ap.add_argument("--peaks", action="store_true",
@@ -307,6 +333,8 @@ def main():
         out["per_config"] = table
     if a.paper_grid:
         out["paper_grid"] = _paper_grid(a.steps, chunk)
+    if a.cold:
+        out["cold"] = _cold(p, min(a.steps, 1000))
     if a.sibling:
         out["sibling"] = _sibling(p, a.steps, chunk)
     if a.peaks:
