@@ -278,8 +278,8 @@ def main():
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE reading is scaled by")
     a = ap.parse_args()
     if a.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (the product needs no exchange between GPUs; "
-                 "see DESIGN.md for how it would shard). Use --gpus 1.")
+        sys.exit("bench.py: this build runs on one GPU only (the product needs no exchange between GPUs: "
+                 "block-rows of W and rows of X both split without one). Use --gpus 1.")
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
