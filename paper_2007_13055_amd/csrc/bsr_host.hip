@@ -38,8 +38,10 @@ size_t plan_bytes(int64_t R, int64_t nnzb)
     // row order (4R bytes) + row descriptors + pair pointers (4R) + pair entries (16 bytes each, at
     // most nnzb/2 + kStripeChunkPairs per block-row), each part padded to 256 bytes, + the k-split
     // kernel's work-item table (up to 2*kMaxKsplitItems + 256 descriptors)
-    const size_t per_row = 4 + 4 * (size_t)kRowDescWords + 4 + 16 * (size_t)kStripeChunkPairs + 16;
-    size_t b = per_row * (size_t)R + 8 * (size_t)nnzb + 2048 + item_table_bytes(R);
+    // small blocks instead: tile-row descriptors (at most one per block-row) and 20 bytes per tile entry
+    // (at most one per stored block)
+    const size_t per_row = 4 + 8 * (size_t)kRowDescWords + 4 + 16 * (size_t)kStripeChunkPairs + 16;
+    size_t b = per_row * (size_t)R + 20 * (size_t)nnzb + 2048 + item_table_bytes(R);
     return (b + 255) & ~(size_t)255;
 }
 
@@ -270,6 +272,67 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
         W->pairs = W->pair_ptr + ptr_words;
         words = (ptr_at + ptr_words + 4 * n_entries + 63) & ~(size_t)63;
     }
+    // Small blocks: group the stored blocks into 16x16 tiles of W.  Tile-row tr covers the block-rows
+    // tr*SR .. tr*SR+SR-1 (SR = 16/bs_r), tile-column tc the block-columns tc*SC .. (SC = 16/bs_c); an
+    // entry is one (tile-row, tile-column) with the byte offsets of its up to SR*SC blocks, position
+    // (sub-row, sub-column) at index sub-row*SC + sub-column.  A second stored block at a position
+    // already taken (duplicates are summed) opens a further entry of the same tile-column.
+    const bool small = (bs_r == 8 || bs_r == 16) && (bs_c == 8 || bs_c == 16) && !(bs_r == 16 && bs_c == 16) &&
+                       n % 16 == 0 && k % 16 == 0 && nnzb > 0 &&
+                       nnzb * bs_r * bs_c * (dtype == BSR_F32 ? 4 : 2) < ((int64_t)1 << 31);
+    if (small) {
+        const int SR = 16 / bs_r, SC = 16 / bs_c;
+        const int64_t TR = n / 16;
+        const int32_t blk_bytes = bs_r * bs_c * (dtype == BSR_F32 ? 4 : 2);
+        struct entry { int32_t tc; int32_t off[4]; };
+        std::vector<std::vector<entry>> rows((size_t)TR);
+        size_t n_entries = 0;
+        for (int64_t tr = 0; tr < TR; ++tr) {
+            auto& list = rows[(size_t)tr];
+            for (int qa = 0; qa < SR; ++qa) {
+                const int64_t r = tr * SR + qa;
+                for (int32_t p = index_pointer_host[r]; p < index_pointer_host[r + 1]; ++p) {
+                    const int32_t tc = block_indices_host[p] / SC, pos = qa * SC + block_indices_host[p] % SC;
+                    entry* slot = nullptr;
+                    for (auto& e : list)
+                        if (e.tc == tc && e.off[pos] == INT32_MIN) { slot = &e; break; }
+                    if (!slot) {
+                        list.push_back(entry{tc, {INT32_MIN, INT32_MIN, INT32_MIN, INT32_MIN}});
+                        slot = &list.back();
+                    }
+                    slot->off[pos] = p * blk_bytes;
+                }
+            }
+            std::stable_sort(list.begin(), list.end(), [](const entry& a, const entry& b) { return a.tc < b.tc; });
+            n_entries += list.size();
+        }
+        std::vector<int32_t> order((size_t)TR);
+        std::iota(order.begin(), order.end(), 0);
+        std::stable_sort(order.begin(), order.end(),
+                         [&](int32_t a, int32_t b) { return rows[(size_t)a].size() > rows[(size_t)b].size(); });
+        const size_t desc_at = words, ent_at = desc_at + (size_t)TR * kRowDescWords;
+        const size_t col_at = ent_at + 4 * n_entries;
+        W->staging.resize(col_at + n_entries + 64, 0);
+        size_t e = 0;
+        for (int64_t s = 0; s < TR; ++s) {
+            const auto& list = rows[(size_t)order[(size_t)s]];
+            int32_t* d = W->staging.data() + desc_at + (size_t)s * kRowDescWords;
+            d[0] = order[(size_t)s];
+            d[1] = (int32_t)e;
+            d[2] = (int32_t)list.size();
+            for (size_t j = 0; j < list.size(); ++j, ++e) {
+                if (j < (size_t)kRowDescCols) d[kRowDescColsAt + j] = list[j].tc;
+                for (int q = 0; q < 4; ++q) W->staging[ent_at + 4 * e + q] = list[j].off[q];
+                W->staging[col_at + e] = list[j].tc;
+            }
+            W->sb_max_entries = std::max<int32_t>(W->sb_max_entries, (int32_t)list.size());
+        }
+        W->sb_desc = W->row_order + desc_at;
+        W->sb_entries = W->row_order + ent_at;
+        W->sb_cols = W->row_order + col_at;
+        W->sb_rows = (int32_t)TR;
+        words = (col_at + n_entries + 63) & ~(size_t)63;
+    }
     {   // the work-item table sits behind everything else, 256-byte aligned
         W->item_desc = const_cast<int32_t*>(W->row_order) + words;
         W->item_capacity = item_table_bytes(R) / (kRowDescWords * sizeof(int32_t));
@@ -307,7 +370,7 @@ bsr_status bsr_query_path(const bsr_matrix* W, int64_t m, bsr_path* path_out)
     // the wavefront-reduction kernels (the paper's own regime, m <= 8) stream W once instead.
     // Thin 16x1 fp32 blocks take the matrix-core path when the caller has lent enough scratch for
     // the transposed copy of X.
-    if (mfma_supports(W) && m >= 16) *path_out = BSR_PATH_MFMA;
+    if ((mfma_supports(W) || mfma_small_supports(W)) && m >= 16) *path_out = BSR_PATH_MFMA;
     else if (mfma_thin_supports(W) && m >= 32 && W->scratch && W->scratch_bytes >= mfma_thin_scratch_bytes(W, m))
         *path_out = BSR_PATH_MFMA;
     else *path_out = BSR_PATH_WAVE;
@@ -351,6 +414,7 @@ bsr_status run_product(const spmm_args& a, bsr_path path, const tune_opts& t)
 {
     if (path == BSR_PATH_MFMA) {
         if (mfma_thin_supports(a.W)) return launch_mfma_thin(a, t);
+        if (mfma_small_supports(a.W)) return launch_mfma_small(a, t);
         if (!mfma_supports(a.W)) return BSR_ERR_UNSUPPORTED;
         return launch_mfma(a, t);
     }
@@ -395,6 +459,10 @@ static std::vector<tuned_choice> tune_candidates(const bsr_matrix* W, int64_t m)
     if (thin) {
         if (W->scratch && W->scratch_bytes >= mfma_thin_scratch_bytes(W, m) && m >= 16)
             for (int a : {4, 6, 8, 10, 12, 14, 16}) add(BSR_PATH_MFMA, 0, 0, 0, a, 0);
+    } else if (mfma_small_supports(W)) {
+        if (m >= 8)
+            for (int nw : {2, 4, 8})
+                for (int per : {1, 2, 4}) add(BSR_PATH_MFMA, 0, nw, 0, per, 0);
     } else if (mfma_supports(W) && m >= 8) {
         add(BSR_PATH_MFMA, 0, 0, 0, 0, 0);                                  // the library's own choice
         for (int mt : {1, 2}) {

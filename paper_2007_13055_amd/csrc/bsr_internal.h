@@ -68,6 +68,15 @@ struct bsr_matrix {
     mutable int item_cus = 0;                // CUs the cached table was laid out for (entry b runs on CU b mod item_cus)
     mutable std::vector<int32_t> item_host;  // host copy (kept alive for the asynchronous upload)
     mutable hipEvent_t item_uploaded = nullptr;   // recorded behind the upload: waited for before item_host changes
+    // Blocks smaller than an MFMA tile (bs_r, bs_c in {8,16}, not both 16; n and k multiples of 16),
+    // grouped into 16x16 tiles of W (see bsr_create): descriptors of the tile-rows, longest first,
+    // [sb_rows][kRowDescWords] = {tile-row, first entry, entries, 0, first tile-columns}; per entry the
+    // byte offsets of the tile's blocks in block_data, [entries][4] (2^31: no block there), and its
+    // tile-column, [entries].
+    const int32_t* sb_desc = nullptr;
+    const int32_t* sb_entries = nullptr;
+    const int32_t* sb_cols = nullptr;
+    int32_t sb_rows = 0, sb_max_entries = 0;
     int32_t max_row_blocks = 0;              // longest block-row
     int32_t long_rows = 0;                   // leading slots whose block count is > 4x the mean and > 8 ("long" bin)
     int32_t empty_rows = 0;                  // block-rows with no stored block
@@ -111,6 +120,8 @@ bsr_status launch_mfma_stripe(const spmm_args& a, const tune_opts& t);
 bool mfma_stripe_supports(const bsr_matrix* W, int tm);   // 16x16 blocks, 16-bit type, tm rows of X fit in LDS
 bsr_status launch_mfma_thin(const spmm_args& a, const tune_opts& t);    // bs_r = 16, bs_c = 1, fp32; needs scratch
 bool mfma_thin_supports(const bsr_matrix* W);
+bsr_status launch_mfma_small(const spmm_args& a, const tune_opts& t);   // bs_r, bs_c in {8,16}, not both 16
+bool mfma_small_supports(const bsr_matrix* W);
 size_t mfma_thin_scratch_bytes(const bsr_matrix* W, int64_t m);   // bytes of the transposed copy of X
 
 // Expands to a chain of `if (shape matches) return FN<T, O, BR, BC>(args...)` over the block

@@ -431,3 +431,55 @@ def test_sibling_product_through_transposed_handle(oracle_mod, case):
     lib.bsr_spmm(WT, Gd, Z)
     torch.cuda.synchronize()
     check(Z.double().cpu().numpy(), Zo, So, p.tau, f"sibling {case}", out_dtype=dtype)
+
+
+@pytest.mark.parametrize("extra", ["", "nw=1,a=1", "nw=8,a=4", "nw=3,a=2"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("bs", [(8, 8), (8, 16), (16, 8)])
+def test_small_blocks_on_matrix_cores(oracle_mod, monkeypatch, extra, dtype, bs):
+    """Blocks below the MFMA tile grouped into 16x16 tiles of W: every shape and type, empty and long
+    tile-rows (more entries than a descriptor's inline columns), duplicates (a second block at a taken
+    position opens a second entry), a ragged last m-tile, and the wave path on the same handle."""
+    import paper_2007_13055_amd as lib
+    if extra:
+        monkeypatch.setenv("BSR_SPMM_TUNE", extra)
+    bs_r, bs_c = bs
+    R, C = 12 * (16 // bs_r), 40 * (16 // bs_c)
+    rng = np.random.default_rng(bs_r * 3 + bs_c)
+    counts = rng.integers(0, 12, size=R)
+    counts[0] = counts[1] = 0                      # an empty tile-row (its block-rows are empty)
+    counts[2] = counts[3] = C                      # a full one: 40 entries > 28 inline columns
+    counts[-1] = 1
+    for m in (16, 45, 300):
+        p = wl.make_problem("sm", m, C * bs_c, R * bs_r, bs_r, bs_c, dtype, dtype, ("counts", counts), ("normal", 1.0),
+                            ("normal", 1.0), 1000 + m + bs_r)
+        Yo, So = oracle_of(oracle_mod, p)
+        Yg, W = gpu_product(p, path=MFMA)
+        assert lib.bsr_query_path(W, m) == MFMA
+        check(Yg, Yo, So, p.tau, f"small {bs} {dtype} m={m} {extra}", out_dtype=dtype)
+        Yw, _ = gpu_product(p, path=WAVE, W=W)
+        check(Yw, Yo, So, p.tau, f"small {bs} {dtype} m={m} wave", out_dtype=dtype)
+    # duplicates and unsorted block-columns
+    ptr = np.array([0, 3, 3, 5, 6], dtype=np.int32)
+    idx = np.array([2, 2, 0, 1, 1, 3], dtype=np.int32)
+    data = wl.round_to_storage(rng.normal(size=(6, bs_r, bs_c)).astype(np.float32), dtype)
+    X = wl.round_to_storage(rng.normal(size=(33, 4 * bs_c)).astype(np.float32), dtype)
+    n4 = 4 * bs_r
+    if n4 % 16 == 0 and (4 * bs_c) % 16 == 0:
+        q = wl.Problem("dup", 33, 4 * bs_c, n4, bs_r, bs_c, dtype, dtype, X, data, idx, ptr)
+        Yo, So = oracle_of(oracle_mod, q)
+        Yg, _ = gpu_product(q, path=MFMA)
+        check(Yg, Yo, So, q.tau, f"small {bs} {dtype} duplicates", out_dtype=dtype)
+
+
+def test_small_blocks_need_whole_tiles():
+    """n or k not a multiple of 16: no tiles, the matrix-core path is refused and AUTO is the wave path."""
+    import torch
+    import paper_2007_13055_amd as lib
+    p = wl.make_problem("odd", 32, 24, 40, 8, 8, "f32", "f32", ("bernoulli", 0.5), ("normal", 1.0), ("normal", 1.0), 5)
+    W = lib.bsr_create(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype="f32")
+    assert lib.bsr_query_path(W, 32) == WAVE
+    X = to_device(p.X, "f32")
+    Y = torch.empty((32, 40), device="cuda")
+    st = lib.load_library().bsr_spmm_ex(W.handle, 32, X.data_ptr(), Y.data_ptr(), 0, MFMA, torch.cuda.current_stream().cuda_stream)
+    assert st == 9                                                # BSR_ERR_UNSUPPORTED
