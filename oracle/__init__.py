@@ -55,6 +55,8 @@ def _load():
         lib.oracle_bsr_spmm_rows.restype = ctypes.c_int
         lib.oracle_bsr_spmm_w.argtypes = [i64, i64, i64, i32, i32, i64, vp, vp, vp, vp, vp, vp]
         lib.oracle_bsr_spmm_w.restype = ctypes.c_int
+        lib.oracle_bsr_sddmm.argtypes = [i64, i64, i64, i32, i32, i64, vp, vp, vp, vp, vp, vp]
+        lib.oracle_bsr_sddmm.restype = ctypes.c_int
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -148,3 +150,27 @@ def bsr_spmm_w(G, block_data, block_indices, index_pointer, k):
     if st != 0:
         raise ValueError("oracle: " + _STATUS.get(st, f"status {st}"))
     return Z, S
+
+
+def bsr_sddmm(G, X, block_indices, index_pointer, b_r, b_c):
+    """Return (D, S), float64 arrays of shape (nnzb, b_r, b_c): the gradient of the stored blocks,
+    D[p] = G[:, block-row of p]^T @ X[:, block-column of p] (G (m, n), X (m, k)), and the same sum over
+    absolute values."""
+    G = _as_f32(G, "G")
+    X = _as_f32(X, "X")
+    if G.ndim != 2 or X.ndim != 2 or G.shape[0] != X.shape[0]:
+        raise ValueError("G must be (m, n) and X (m, k)")
+    m, n = G.shape
+    k = X.shape[1]
+    idx = np.ascontiguousarray(np.asarray(block_indices, dtype=np.int32).reshape(-1))
+    ptr = np.ascontiguousarray(np.asarray(index_pointer, dtype=np.int32).reshape(-1))
+    nnzb = idx.shape[0]
+    if b_r <= 0 or b_c <= 0 or n % b_r != 0 or ptr.shape[0] != n // b_r + 1:
+        raise ValueError("index_pointer must have n / b_r + 1 entries with b_r | n")
+    D = np.zeros((nnzb, b_r, b_c), dtype=np.float64)
+    S = np.zeros((nnzb, b_r, b_c), dtype=np.float64)
+    st = _load().oracle_bsr_sddmm(m, k, n, b_r, b_c, nnzb, G.ctypes.data, X.ctypes.data,
+                                  idx.ctypes.data, ptr.ctypes.data, D.ctypes.data, S.ctypes.data)
+    if st != 0:
+        raise ValueError("oracle: " + _STATUS.get(st, f"status {st}"))
+    return D, S

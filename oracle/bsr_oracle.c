@@ -202,3 +202,49 @@ int oracle_bsr_spmm_w(int64_t m, int64_t k, int64_t n, int32_t b_r, int32_t b_c,
     }
     return ORACLE_OK;
 }
+
+/*
+ * The sampled sibling: the gradient of the stored blocks,
+ *
+ *   D[p][a][c] = sum over i in [0, m) of  G[i][r*b_r + a] * X[i][block_indices[p]*b_c + c]
+ *
+ * for every stored block p of block-row r -- the entries of G^T X at the positions W stores, and
+ * nothing else (positions of W without a stored block have no gradient).  It follows from the
+ * same definition: Y = X W^T is linear in block_data[p][a][c] with coefficient X[i][col*b_c + c]
+ * in Y[i][r*b_r + a].  D has the shape of block_data; S is the same sum over absolute values.
+ * Order: i ascending; double throughout.
+ */
+int oracle_bsr_sddmm(int64_t m, int64_t k, int64_t n, int32_t b_r, int32_t b_c, int64_t nnzb,
+                     const float* G, const float* X,
+                     const int32_t* block_indices, const int32_t* index_pointer,
+                     double* D, double* S)
+{
+    if (m < 0) return ORACLE_BAD_ARGUMENT;
+    int st = check_structure(k, n, b_r, b_c, nnzb, block_indices, index_pointer);
+    if (st != ORACLE_OK) return st;
+    if (nnzb == 0) return ORACLE_OK;
+    if (!D || (m > 0 && (!G || !X))) return ORACLE_BAD_ARGUMENT;
+
+    const int64_t R = n / b_r;
+    const int64_t block_elems = (int64_t)b_r * b_c;
+
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t r = 0; r < R; ++r) {
+        for (int64_t p = index_pointer[r]; p < index_pointer[r + 1]; ++p) {
+            const int64_t col0 = (int64_t)block_indices[p] * b_c;
+            for (int32_t a = 0; a < b_r; ++a) {
+                for (int32_t c = 0; c < b_c; ++c) {
+                    double d = 0.0, s = 0.0;
+                    for (int64_t i = 0; i < m; ++i) {
+                        const double prod = (double)G[i * n + r * b_r + a] * (double)X[i * k + col0 + c];
+                        d += prod;
+                        s += fabs(prod);
+                    }
+                    D[p * block_elems + (int64_t)a * b_c + c] = d;
+                    if (S) S[p * block_elems + (int64_t)a * b_c + c] = s;
+                }
+            }
+        }
+    }
+    return ORACLE_OK;
+}

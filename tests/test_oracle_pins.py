@@ -325,3 +325,49 @@ def test_sibling_empty_block_columns_are_exact_zero(oracle_mod):
     Z, S = oracle_mod.bsr_spmm_w(G, data, idx, ptr, 8)
     assert np.all(Z[:, 2:4] == 0) and np.all(Z[:, 6:8] == 0) and np.all(S[:, 2:4] == 0)
     assert np.all(S[:, 0:2] > 0)
+
+
+# ---------------------------------------------------------------- the sampled sibling D = (G^T X) at the stored blocks
+def test_sampled_hand_worked_fixture(oracle_mod):
+    """Catches: block-row / block-column swapped, a/c swapped inside a block, a lost row of the sum."""
+    with open(os.path.join(GOLDEN, "hand_worked_2x2.json")) as f:
+        g = json.load(f)
+    D, S = oracle_mod.bsr_sddmm(np.array(g["G"], dtype=np.float32), np.array(g["X"], dtype=np.float32),
+                                g["block_indices"], g["index_pointer"], g["bs_r"], g["bs_c"])
+    assert np.array_equal(D, np.array(g["D"], dtype=np.float64))
+    assert np.array_equal(S, np.array(g["S_D"], dtype=np.float64))
+
+
+@pytest.mark.parametrize("shape", [(5, 24, 18, 3, 4, 0.4), (40, 32, 48, 16, 16, 0.3), (7, 40, 64, 16, 1, 0.2), (1, 8, 8, 1, 1, 0.5)])
+def test_sampled_matches_dense_gemm(oracle_mod, shape):
+    """Every stored block against the same slice of numpy's G^T @ X in double."""
+    m, k, n, bs_r, bs_c, d = shape
+    p = rand_problem(41 + m, m, k, n, bs_r, bs_c, d)
+    G = np.random.default_rng(m).normal(size=(m, n)).astype(np.float32)
+    D, S = oracle_mod.bsr_sddmm(G, p.X, p.block_indices, p.index_pointer, bs_r, bs_c)
+    full = G.astype(np.float64).T @ p.X.astype(np.float64)
+    full_s = np.abs(G.astype(np.float64)).T @ np.abs(p.X.astype(np.float64))
+    for r in range(n // bs_r):
+        for q in range(int(p.index_pointer[r]), int(p.index_pointer[r + 1])):
+            c = int(p.block_indices[q])
+            ref = full[r * bs_r:(r + 1) * bs_r, c * bs_c:(c + 1) * bs_c]
+            assert np.all(np.abs(D[q] - ref) <= 1e-12 * (S[q] + 1e-300))
+            assert np.all(np.abs(S[q] - full_s[r * bs_r:(r + 1) * bs_r, c * bs_c:(c + 1) * bs_c]) <= 1e-12 * (S[q] + 1e-300))
+
+
+def test_sampled_is_the_gradient_of_the_forward_product(oracle_mod):
+    """<X V^T, G> = <V, D> for any block values V on W's pattern: Y is linear in the stored blocks and D is
+    the coefficient.  Ties the third oracle function to the first through the mathematics."""
+    p = rand_problem(88, 9, 48, 40, 8, 16, 0.35)
+    G = np.random.default_rng(6).normal(size=(p.m, p.n)).astype(np.float32)
+    Y, _ = run(oracle_mod, p)
+    D, _ = oracle_mod.bsr_sddmm(G, p.X, p.block_indices, p.index_pointer, p.bs_r, p.bs_c)
+    lhs, rhs = float(np.sum(Y * G)), float(np.sum(p.block_data.astype(np.float64) * D))
+    assert abs(lhs - rhs) <= 1e-10 * (abs(lhs) + 1.0)
+
+
+def test_sampled_all_ones_and_duplicates(oracle_mod):
+    """G = 1, X = 1: every entry of every stored block is m; duplicate blocks get the same values."""
+    ptr, idx = np.array([0, 2, 2, 3], np.int32), np.array([1, 1, 0], np.int32)
+    D, S = oracle_mod.bsr_sddmm(np.ones((7, 9), np.float32), np.ones((7, 4), np.float32), idx, ptr, 3, 2)
+    assert np.all(D == 7) and np.all(S == 7) and D.shape == (3, 3, 2)
