@@ -171,9 +171,9 @@ def _paper_grid(steps, chunk):
 
 
 def _sibling(p, steps, chunk):
-    """The sibling product Z = G * W (gradient of the layer's input) on workload p: the same kernels on
-    the handle of W^T; also the time of re-transposing the block values on the device (needed once
-    per update of W)."""
+    """The sibling products on workload p: Z = G * W (gradient of the layer's input; the same kernels on
+    the handle of W^T, plus the time of re-transposing the block values on the device, needed once per
+    update of W) and the sampled product D = (G^T X) at the stored blocks (gradient of the blocks)."""
     import torch
     import numpy as np
     import paper_2007_13055_amd as lib
@@ -191,9 +191,14 @@ def _sibling(p, steps, chunk):
     tr = lambda: so.bsr_transpose_values(code, p.bs_r, p.bs_c, p.nnzb, perm_dev.data_ptr(), src.data_ptr(),
                                          dst.data_ptr(), stream())
     _, ev_t, _ = _time_steps(tr, steps, 20, chunk)
-    s = ev / steps
+    # the sampled sibling D[p] = G[:, block-row]^T X[:, block-column] (gradient of the stored blocks)
+    W, X, _ = _upload(p)
+    D = torch.empty((p.nnzb, p.bs_r, p.bs_c), dtype=tdt[p.out_dtype], device="cuda")
+    _, ev_d, _ = _time_steps(lambda: lib.bsr_sddmm(W, G, X, D, d_dtype=p.out_dtype), steps, 20, chunk)
+    s, sd = ev / steps, ev_d / steps
     return {"us_per_product": s * 1e6, "tflops": p.flops / s / 1e12, "launch": mode,
-            "transpose_values_us": ev_t / steps * 1e6}
+            "transpose_values_us": ev_t / steps * 1e6,
+            "sampled_us_per_product": sd * 1e6, "sampled_tflops": p.flops / sd / 1e12}
 
 
 def _cold(p, steps):

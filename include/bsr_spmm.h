@@ -206,6 +206,22 @@ bsr_status bsr_transpose_pattern(int64_t n, int64_t k, int32_t bs_r, int32_t bs_
 bsr_status bsr_transpose_values(bsr_dtype dtype, int32_t bs_r, int32_t bs_c, int64_t nnzb, const int32_t* perm_dev,
                                 const void* block_data_dev, void* t_block_data_dev, void* hip_stream);
 
+/*
+ * The sampled sibling: the gradient of the stored blocks.  With Y = X * W^T a layer's forward pass
+ * and G = dL/dY, Y is linear in block_data[p][a][c] with coefficient X[i][col*bs_c + c] in
+ * Y[i][r*bs_r + a], so
+ *     D[p][a][c] = sum over i of  G[i][r*bs_r + a] * X[i][block_indices[p]*bs_c + c]
+ * for every stored block p of block-row r: the entries of G^T X at the positions W stores.
+ *   G_dev   DEVICE, m*n elements of W's dtype, row-major     X_dev  DEVICE, m*k elements, row-major
+ *   D_dev   DEVICE, nnzb*bs_r*bs_c elements of d_dtype (W's dtype or BSR_F32), the layout of
+ *           block_data; every element is written; fp32 accumulation, rounded to nearest-even
+ * Block shapes with bs_r, bs_c in {16, 32, 64} run on the matrix cores, any other shape on a plain
+ * loop.  Asynchronous on hip_stream; reads W's pattern only, not its values.
+ * Errors: NULL, SHAPE (m < 0 or m*max(k,n) >= 2^31), DTYPE, ALIGN, HIP.
+ */
+bsr_status bsr_sddmm(const bsr_matrix* W, int64_t m, const void* G_dev, const void* X_dev, void* D_dev,
+                     bsr_dtype d_dtype, void* hip_stream);
+
 /* Static, human-readable text for a status code. */
 const char* bsr_status_string(bsr_status s);
 

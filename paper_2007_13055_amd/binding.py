@@ -54,6 +54,7 @@ def load_library():
     lib.bsr_set_scratch.argtypes = [vp, vp, sz]
     lib.bsr_transpose_pattern.argtypes = [i64, i64, i32, i32, i64, vp, vp, vp, vp, vp]
     lib.bsr_transpose_values.argtypes = [ctypes.c_int, i32, i32, i64, vp, vp, vp, vp]
+    lib.bsr_sddmm.argtypes = [vp, i64, vp, vp, vp, ctypes.c_int, vp]
     lib.bsr_status_string.argtypes = [ctypes.c_int]
     lib.bsr_status_string.restype = ctypes.c_char_p
     for f in ("bsr_validate", "bsr_workspace_size", "bsr_create", "bsr_spmm", "bsr_spmm_ex", "bsr_query_path",
@@ -269,6 +270,27 @@ def bsr_tune_result(W: BsrMatrix, m: int, y_dtype=None):
         raise BsrError(st, "bsr_tune_result")
     keys = ("path", "variant", "nw", "mt", "a", "b")
     return {**{k: int(v) for k, v in zip(keys, out)}, "us": float(us.value)}
+
+
+def bsr_sddmm(W: BsrMatrix, G, X, D=None, d_dtype=None):
+    """D[p] = G[:, block-row of p]^T @ X[:, block-column of p] for every stored block of W (the gradient
+    of the block values); G (m, n), X (m, k) device tensors of W's dtype.  Returns D (nnzb, bs_r, bs_c)."""
+    import torch
+    if G.dim() != 2 or X.dim() != 2 or G.shape[0] != X.shape[0] or G.shape[1] != W.n or X.shape[1] != W.k:
+        raise ValueError("G must be (m, n) and X (m, k)")
+    if _dtype_name(G) != W.dtype or _dtype_name(X) != W.dtype or not G.is_contiguous() or not X.is_contiguous():
+        raise ValueError("G and X must be contiguous and of W's dtype")
+    d_dtype = d_dtype or W.dtype
+    nnzb = int(W.block_data.shape[0]) if W.block_data.dim() == 3 else 0
+    if D is None:
+        D = torch.empty((nnzb, W.bs_r, W.bs_c), dtype=_torch_dtype(d_dtype), device=G.device)
+    elif tuple(D.shape) != (nnzb, W.bs_r, W.bs_c) or _dtype_name(D) != d_dtype or not D.is_contiguous():
+        raise ValueError("D must be a contiguous (nnzb, bs_r, bs_c) tensor of d_dtype")
+    st = load_library().bsr_sddmm(W.handle, int(G.shape[0]), G.data_ptr(), X.data_ptr(), D.data_ptr(),
+                                  _DTYPE_CODE[d_dtype], torch.cuda.current_stream().cuda_stream)
+    if st != 0:
+        raise BsrError(st, "bsr_sddmm")
+    return D
 
 
 def bsr_scratch_size(W: BsrMatrix, m: int) -> int:

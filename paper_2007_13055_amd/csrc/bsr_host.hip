@@ -41,7 +41,8 @@ size_t plan_bytes(int64_t R, int64_t nnzb)
     // small blocks instead: tile-row descriptors (at most one per block-row) and 20 bytes per tile entry
     // (at most one per stored block)
     const size_t per_row = 4 + 8 * (size_t)kRowDescWords + 4 + 16 * (size_t)kStripeChunkPairs + 16;
-    size_t b = per_row * (size_t)R + 20 * (size_t)nnzb + 2048 + item_table_bytes(R);
+    // + 4 bytes per stored block: its block-row (the sampled product starts from a block)
+    size_t b = per_row * (size_t)R + 24 * (size_t)nnzb + 2560 + item_table_bytes(R);
     return (b + 255) & ~(size_t)255;
 }
 
@@ -332,6 +333,14 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
         W->sb_cols = W->row_order + col_at;
         W->sb_rows = (int32_t)TR;
         words = (col_at + n_entries + 63) & ~(size_t)63;
+    }
+    if (nnzb > 0) {                                   // block-row of every stored block
+        const size_t at = words;
+        W->staging.resize(at + (size_t)nnzb + 64, 0);
+        for (int64_t r = 0; r < R; ++r)
+            for (int32_t p = index_pointer_host[r]; p < index_pointer_host[r + 1]; ++p) W->staging[at + (size_t)p] = (int32_t)r;
+        W->block_row = W->row_order + at;
+        words = (at + (size_t)nnzb + 63) & ~(size_t)63;
     }
     {   // the work-item table sits behind everything else, 256-byte aligned
         W->item_desc = const_cast<int32_t*>(W->row_order) + words;

@@ -73,6 +73,7 @@ struct bsr_matrix {
     // [sb_rows][kRowDescWords] = {tile-row, first entry, entries, 0, first tile-columns}; per entry the
     // byte offsets of the tile's blocks in block_data, [entries][4] (2^31: no block there), and its
     // tile-column, [entries].
+    const int32_t* block_row = nullptr;      // device, [nnzb]: block-row of every stored block (sampled product)
     const int32_t* sb_desc = nullptr;
     const int32_t* sb_entries = nullptr;
     const int32_t* sb_cols = nullptr;

@@ -1,0 +1,275 @@
+// The sampled sibling: D[p] = G[:, block-row of p]^T * X[:, block-column of p] for every stored
+// block p -- the gradient of the block values when Y = X * W^T is a layer's forward pass (Y is
+// linear in block_data[p][a][c] with coefficient X[i][col*bs_c + c] in Y[i][r*bs_r + a]).
+//
+// One workgroup (4 wavefronts) per stored block.  The reduction runs over the rows i of G and X,
+// which is the slow axis of both, so the operands cannot be read in MFMA order from memory.  A
+// wavefront takes every fourth chunk of 32 rows: it copies the 32 x bs_r piece of G and the
+// 32 x bs_c piece of X into its own LDS area with contiguous 16-byte reads (the next chunk's loads
+// are in flight while this one is multiplied), and reads the operands back transposed -- 16-bit
+// types with the LDS transpose read (ds_read_b64_tr_b16: each lane receives, for its row of the
+// MFMA operand, 4 consecutive values of the reduction index), fp32 one value per lane and MFMA
+// step.  Every wavefront accumulates the whole bs_r x bs_c block over its chunks; the four partial
+// blocks are added through LDS in fixed order and stored as one contiguous block.
+// Other block shapes: one thread per element of the block, a plain loop over i.
+#include <algorithm>
+
+#include "bsr_mfma_common.h"
+
+using namespace bsr_dev;
+
+namespace {
+
+constexpr int kChunk = 32;                            // rows of G and X per step of a wavefront
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+template <typename T, int BS_R, int BS_C>
+struct sddmm_geom {
+    static constexpr int S = (int)sizeof(T);
+    static constexpr int MM = (BS_R >= 32 && BS_C >= 32) ? 32 : 16;   // MFMA tile edge
+    static constexpr int NA = BS_R / MM, NC = BS_C / MM;
+    static constexpr int RBG = BS_R * S, RBC = BS_C * S;               // bytes of a row of the G / X piece
+    static constexpr int PG = RBG + 16, PC = RBC + 16;                 // padded LDS rows
+    static constexpr int NLG = kChunk * RBG / 1024, NLX = kChunk * RBC / 1024;   // 1 KiB loads per chunk
+    static constexpr int LDP = BS_C + 4;                               // padded row of the fp32 partial block
+    static constexpr int STAGE = kChunk * (PG + PC);
+    static constexpr int PART = BS_R * LDP * 4;
+    static constexpr int REGION = ((STAGE > PART ? STAGE : PART) + 15) & ~15;
+};
+
+// The lane's 8 consecutive reduction-index values of operand row `row0 + lane's row`, 16-bit types.
+//   tile   [kChunk][pitch] bytes, row-major pieces of G or X as they lie in memory
+//   MM=32: lane l = 32*kappa + 16*beta + lambda feeds MFMA row 16*beta + lambda, values i0 + 8*kappa .. +7
+//   MM=16: lane l = 16*g + lambda feeds MFMA row lambda, values i0 + 8*g .. +7
+// ds_read_b64_tr_b16 works on groups of 16 lanes: lane mu supplies the address of 4 consecutive
+// 16-bit values, and lane lambda receives value (lambda mod 4) of the lanes lambda/4 + 4j, j = 0..3.
+// With lane mu pointing at row (mu div 4) and columns 4*(mu mod 4) .. +3 of a 4 x 16 piece, lane
+// lambda therefore receives column lambda of its 4 rows: the transpose an MFMA operand needs.
+template <typename T, int MM>
+__device__ __forceinline__ u32x4 read_operand16(const unsigned char* tile, int pitch, int i0, int col0, int lane)
+{
+    const int lambda = lane & 15;
+    int irow, ccol;
+    if constexpr (MM == 32) {
+        irow = i0 + 8 * (lane >> 5) + (lambda >> 2);
+        ccol = col0 + 16 * ((lane >> 4) & 1) + 4 * (lambda & 3);
+    } else {
+        irow = i0 + 8 * (lane >> 4) + (lambda >> 2);
+        ccol = col0 + 4 * (lambda & 3);
+    }
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const unsigned char* p0 = tile + irow * pitch + ccol * 2;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p0));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p0 + 4 * pitch));
+    const u32x2 a = __builtin_bit_cast(u32x2, lo), b = __builtin_bit_cast(u32x2, hi);
+    return u32x4{a.x, a.y, b.x, b.y};
+}
+
+template <typename T, typename O, int BS_R, int BS_C>
+__global__ __launch_bounds__(256) void bsr_sddmm_mfma(const T* __restrict__ G, const T* __restrict__ X,
+                                                      const int32_t* __restrict__ block_row,
+                                                      const int32_t* __restrict__ indices, O* __restrict__ D,
+                                                      int m, int k, int n)
+{
+    typedef sddmm_geom<T, BS_R, BS_C> geo;
+    constexpr int S = geo::S, MM = geo::MM, NA = geo::NA, NC = geo::NC;
+    constexpr int RBG = geo::RBG, RBC = geo::RBC, PG = geo::PG, PC = geo::PC, NLG = geo::NLG, NLX = geo::NLX;
+    constexpr int LDP = geo::LDP;
+    static_assert(NLG >= 1 && NLX >= 1, "a chunk of either piece is at least one load per lane");
+    typedef typename AccT<MM>::type acc_t;
+    constexpr int NE = MM == 32 ? 16 : 4;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];   // [4 wavefronts][REGION]
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int p = blockIdx.x;
+    const int r = block_row[p], c = indices[p];       // uniform: scalar reads
+    unsigned char* gt = lds + (size_t)wave * geo::REGION;     // G piece [kChunk][PG]
+    unsigned char* xt = gt + kChunk * PG;                     // X piece [kChunk][PC]
+
+    acc_t acc[NA][NC];
+#pragma unroll
+    for (int ua = 0; ua < NA; ++ua)
+#pragma unroll
+        for (int uc = 0; uc < NC; ++uc)
+#pragma unroll
+            for (int e = 0; e < NE; ++e) acc[ua][uc][e] = 0.f;
+
+    // lane's pieces of a chunk: piece t*64 + lane is 16 bytes of row (piece div pieces-per-row)
+    const unsigned char* gbase = reinterpret_cast<const unsigned char*>(G + (size_t)r * BS_R);
+    const unsigned char* xbase = reinterpret_cast<const unsigned char*>(X + (size_t)c * BS_C);
+    const size_t grow = (size_t)n * S, xrow = (size_t)k * S;
+    int g_row[NLG], g_cb[NLG], x_row[NLX], x_cb[NLX];
+#pragma unroll
+    for (int t = 0; t < NLG; ++t) { const int q = t * 64 + lane; g_row[t] = q / (RBG / 16); g_cb[t] = (q % (RBG / 16)) * 16; }
+#pragma unroll
+    for (int t = 0; t < NLX; ++t) { const int q = t * 64 + lane; x_row[t] = q / (RBC / 16); x_cb[t] = (q % (RBC / 16)) * 16; }
+
+    u32x4 gg[NLG], gx[NLX];
+    auto fetch = [&](int i0) {                        // rows past m repeat row m-1 and are zeroed when staged
+#pragma unroll
+        for (int t = 0; t < NLG; ++t)
+            gg[t] = *reinterpret_cast<const u32x4*>(gbase + (size_t)min(i0 + g_row[t], m - 1) * grow + g_cb[t]);
+#pragma unroll
+        for (int t = 0; t < NLX; ++t)
+            gx[t] = *reinterpret_cast<const u32x4*>(xbase + (size_t)min(i0 + x_row[t], m - 1) * xrow + x_cb[t]);
+    };
+    auto stage = [&](int i0) {
+        const bool tail = i0 + kChunk > m;            // uniform
+#pragma unroll
+        for (int t = 0; t < NLG; ++t) {
+            u32x4 v = gg[t];
+            if (tail && i0 + g_row[t] >= m) v = u32x4{0u, 0u, 0u, 0u};
+            *reinterpret_cast<u32x4*>(gt + g_row[t] * PG + g_cb[t]) = v;
+        }
+#pragma unroll
+        for (int t = 0; t < NLX; ++t) {
+            u32x4 v = gx[t];
+            if (tail && i0 + x_row[t] >= m) v = u32x4{0u, 0u, 0u, 0u};
+            *reinterpret_cast<u32x4*>(xt + x_row[t] * PC + x_cb[t]) = v;
+        }
+    };
+    auto compute = [&]() {
+        if constexpr (std::is_same<T, float>::value) {
+            constexpr int KS = MM == 32 ? 2 : 4;      // reduction steps per MFMA
+            const int irow = lane / MM, col = lane % MM;
+#pragma unroll
+            for (int s = 0; s < kChunk / KS; ++s) {
+                float av[NA], bv[NC];
+#pragma unroll
+                for (int ua = 0; ua < NA; ++ua) av[ua] = *reinterpret_cast<const float*>(gt + (s * KS + irow) * PG + (ua * MM + col) * 4);
+#pragma unroll
+                for (int uc = 0; uc < NC; ++uc) bv[uc] = *reinterpret_cast<const float*>(xt + (s * KS + irow) * PC + (uc * MM + col) * 4);
+#pragma unroll
+                for (int ua = 0; ua < NA; ++ua)
+#pragma unroll
+                    for (int uc = 0; uc < NC; ++uc) {
+                        if constexpr (MM == 32) acc[ua][uc] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[ua], bv[uc], acc[ua][uc], 0, 0, 0);
+                        else                    acc[ua][uc] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ua], bv[uc], acc[ua][uc], 0, 0, 0);
+                    }
+            }
+        } else {
+            constexpr int KI = MM == 32 ? 16 : 32;    // rows of the chunk one MFMA reduces over
+#pragma unroll
+            for (int s = 0; s < kChunk / KI; ++s) {
+                Frag<T, 8> af[NA], bf[NC];
+#pragma unroll
+                for (int ua = 0; ua < NA; ++ua) {
+                    const u32x4 v = read_operand16<T, MM>(gt, PG, s * KI, ua * MM, lane);
+                    af[ua].w[0] = v.x; af[ua].w[1] = v.y; af[ua].w[2] = v.z; af[ua].w[3] = v.w;
+                }
+#pragma unroll
+                for (int uc = 0; uc < NC; ++uc) {
+                    const u32x4 v = read_operand16<T, MM>(xt, PC, s * KI, uc * MM, lane);
+                    bf[uc].w[0] = v.x; bf[uc].w[1] = v.y; bf[uc].w[2] = v.z; bf[uc].w[3] = v.w;
+                }
+#pragma unroll
+                for (int ua = 0; ua < NA; ++ua)
+#pragma unroll
+                    for (int uc = 0; uc < NC; ++uc) mfma_frag<T, MM, 8>(acc[ua][uc], af[ua], bf[uc]);
+            }
+        }
+    };
+
+    // chunks wave, wave + 4, ...: the next chunk's loads are issued once this one's registers are in LDS
+    const int n_chunks = (m + kChunk - 1) / kChunk;
+    if (wave < n_chunks) fetch(wave * kChunk);
+    for (int q = wave; q < n_chunks; q += 4) {
+        stage(q * kChunk);
+        if (q + 4 < n_chunks) fetch((q + 4) * kChunk);
+        compute();
+    }
+
+    // partial block of this wavefront -> its LDS area as [bs_r][LDP] fp32 (the staged pieces are consumed:
+    // the wavefront's own LDS operations complete in order)
+    float* part = reinterpret_cast<float*>(gt);
+#pragma unroll
+    for (int ua = 0; ua < NA; ++ua)
+#pragma unroll
+        for (int uc = 0; uc < NC; ++uc)
+#pragma unroll
+            for (int e = 0; e < NE; ++e) {
+                int a, cc;
+                if constexpr (MM == 32) { a = ua * 32 + 8 * (e / 4) + 4 * (lane / 32) + e % 4; cc = uc * 32 + lane % 32; }
+                else                    { a = ua * 16 + 4 * (lane / 16) + e;                    cc = uc * 16 + lane % 16; }
+                part[a * LDP + cc] = acc[ua][uc][e];
+            }
+    __syncthreads();
+
+    // fixed-order sum of the four partial blocks, 4 consecutive columns per thread, contiguous store
+    O* dst = D + (size_t)p * (BS_R * BS_C);
+    for (int e4 = threadIdx.x; e4 < BS_R * BS_C / 4; e4 += 256) {
+        const int a = (e4 * 4) / BS_C, cc = (e4 * 4) % BS_C;
+        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            s += *reinterpret_cast<const f32x4*>(lds + (size_t)w * geo::REGION + ((size_t)a * LDP + cc) * 4);
+        store4<O>(dst + e4 * 4, s.x, s.y, s.z, s.w);
+    }
+}
+
+// Any block shape: thread e of the workgroup owns elements e, e + 256, ... of the block.
+template <typename T, typename O>
+__global__ __launch_bounds__(256) void bsr_sddmm_generic(const T* __restrict__ G, const T* __restrict__ X,
+                                                         const int32_t* __restrict__ block_row,
+                                                         const int32_t* __restrict__ indices, O* __restrict__ D,
+                                                         int m, int k, int n, int bs_r, int bs_c)
+{
+    const int p = blockIdx.x;
+    const int r = block_row[p], c = indices[p];
+    for (int e = threadIdx.x; e < bs_r * bs_c; e += 256) {
+        const int a = e / bs_c, cc = e - a * bs_c;
+        const T* g = G + (size_t)r * bs_r + a;
+        const T* x = X + (size_t)c * bs_c + cc;
+        float acc = 0.f;
+        for (int i = 0; i < m; ++i) acc = fmaf((float)g[(size_t)i * n], (float)x[(size_t)i * k], acc);
+        D[(size_t)p * bs_r * bs_c + e] = (O)acc;
+    }
+}
+
+template <typename T, typename O, int BS_R, int BS_C>
+bsr_status launch_sddmm_shape(const bsr_matrix* W, int m, const void* G, const void* X, void* D, hipStream_t stream)
+{
+    typedef sddmm_geom<T, BS_R, BS_C> geo;
+    const size_t lds = 4 * (size_t)geo::REGION;
+    static const hipError_t attr =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&bsr_sddmm_mfma<T, O, BS_R, BS_C>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (attr != hipSuccess) return BSR_ERR_HIP;
+    hipLaunchKernelGGL((bsr_sddmm_mfma<T, O, BS_R, BS_C>), dim3((unsigned)W->nnzb), dim3(256), lds, stream,
+                       (const T*)G, (const T*)X, W->block_row, W->indices, (O*)D, m, (int)W->k, (int)W->n);
+    return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
+}
+
+template <typename T, typename O>
+bsr_status launch_sddmm_types(const bsr_matrix* W, int m, const void* G, const void* X, void* D, hipStream_t stream)
+{
+    const int br = W->bs_r, bc = W->bs_c;
+    BSR_MFMA_SHAPES(launch_sddmm_shape, T, O, br, bc, W, m, G, X, D, stream);
+    hipLaunchKernelGGL((bsr_sddmm_generic<T, O>), dim3((unsigned)W->nnzb), dim3(256), 0, stream,
+                       (const T*)G, (const T*)X, W->block_row, W->indices, (O*)D, m, (int)W->k, (int)W->n, br, bc);
+    return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" bsr_status bsr_sddmm(const bsr_matrix* W, int64_t m, const void* G_dev, const void* X_dev, void* D_dev,
+                                bsr_dtype d_dtype, void* hip_stream)
+{
+    if (!W) return BSR_ERR_NULL;
+    if (m < 0) return BSR_ERR_SHAPE;
+    if (d_dtype != W->dtype && d_dtype != BSR_F32) return BSR_ERR_DTYPE;
+    if (W->nnzb == 0) return BSR_OK;
+    if (!D_dev || (m > 0 && (!G_dev || !X_dev))) return BSR_ERR_NULL;
+    if (m * std::max<int64_t>(W->k, W->n) >= ((int64_t)1 << 31)) return BSR_ERR_SHAPE;
+    if (((uintptr_t)G_dev | (uintptr_t)X_dev | (uintptr_t)D_dev) & 15u) return BSR_ERR_ALIGN;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    // m == 0 needs no special case: the kernels then read nothing and store zeros (an empty sum)
+    const int mi = (int)m;
+    if (W->dtype == BSR_F32) return launch_sddmm_types<float, float>(W, mi, G_dev, X_dev, D_dev, stream);
+    if (W->dtype == BSR_F16) return d_dtype == BSR_F32 ? launch_sddmm_types<_Float16, float>(W, mi, G_dev, X_dev, D_dev, stream)
+                                                       : launch_sddmm_types<_Float16, _Float16>(W, mi, G_dev, X_dev, D_dev, stream);
+    return d_dtype == BSR_F32 ? launch_sddmm_types<__bf16, float>(W, mi, G_dev, X_dev, D_dev, stream)
+                              : launch_sddmm_types<__bf16, __bf16>(W, mi, G_dev, X_dev, D_dev, stream);
+}

@@ -483,3 +483,39 @@ def test_small_blocks_need_whole_tiles():
     Y = torch.empty((32, 40), device="cuda")
     st = lib.load_library().bsr_spmm_ex(W.handle, 32, X.data_ptr(), Y.data_ptr(), 0, MFMA, torch.cuda.current_stream().cuda_stream)
     assert st == 9                                                # BSR_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("dtype,out", [("f32", "f32"), ("f16", "f16"), ("bf16", "bf16"), ("bf16", "f32")])
+@pytest.mark.parametrize("bs", SHAPES + [(8, 8), (16, 1), (3, 5)])
+def test_sampled_product_block_gradients(oracle_mod, dtype, out, bs):
+    """D[p] = G[:, block-row]^T X[:, block-column] for every stored block, against the oracle: every matrix-core
+    shape and three shapes of the plain loop; m below one chunk, one chunk per wavefront, a ragged tail, many."""
+    import torch
+    import paper_2007_13055_amd as lib
+    bs_r, bs_c = bs
+    R, C = 5, 6
+    for m in (1, 37, 128, 300):
+        p = wl.make_problem("sd", m, C * bs_c, R * bs_r, bs_r, bs_c, dtype, dtype, ("bernoulli", 0.5), ("normal", 1.0),
+                            ("normal", 1.0), 1100 + m + bs_r + bs_c)
+        G = wl.round_to_storage(np.random.default_rng(m).normal(size=(m, p.n)).astype(np.float32), dtype)
+        Do, So = oracle_mod.bsr_sddmm(G, p.X, p.block_indices, p.index_pointer, bs_r, bs_c)
+        W = lib.bsr_create(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype=dtype)
+        D = torch.full((p.nnzb, bs_r, bs_c), float("nan"), dtype=getattr(torch, {"f32": "float32", "f16": "float16", "bf16": "bfloat16"}[out]),
+                       device="cuda")
+        lib.bsr_sddmm(W, to_device(G, dtype), to_device(p.X, dtype), D, d_dtype=out)
+        torch.cuda.synchronize()
+        check(D.double().cpu().numpy().reshape(p.nnzb, -1), Do.reshape(p.nnzb, -1), So.reshape(p.nnzb, -1), p.tau,
+              f"sampled {bs} {dtype}->{out} m={m}", out_dtype=out)
+
+
+def test_sampled_product_small_integers_bitwise(oracle_mod):
+    """Integer-valued G and X: every partial sum is exact in fp32, so the block gradients match bit for bit."""
+    import torch
+    import paper_2007_13055_amd as lib
+    p = wl.small_integer_problem(200, 4 * 64, 3 * 32, 32, 64, 0.6, seed=31, in_dtype="f16", out_dtype="f32", lo=-2, hi=2)
+    G = np.random.default_rng(3).integers(-2, 3, size=(p.m, p.n)).astype(np.float32)
+    Do, _ = oracle_mod.bsr_sddmm(G, p.X, p.block_indices, p.index_pointer, p.bs_r, p.bs_c)
+    W = lib.bsr_create(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype="f16")
+    D = lib.bsr_sddmm(W, to_device(G, "f16"), to_device(p.X, "f16"), d_dtype="f32")
+    torch.cuda.synchronize()
+    assert np.array_equal(D.double().cpu().numpy(), Do)
