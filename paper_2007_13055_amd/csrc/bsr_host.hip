@@ -41,8 +41,8 @@ size_t plan_bytes(int64_t R, int64_t nnzb)
     // small blocks instead: tile-row descriptors (at most one per block-row) and 20 bytes per tile entry
     // (at most one per stored block)
     const size_t per_row = 4 + 8 * (size_t)kRowDescWords + 4 + 16 * (size_t)kStripeChunkPairs + 16;
-    // + 4 bytes per stored block: its block-row (the sampled product starts from a block)
-    size_t b = per_row * (size_t)R + 24 * (size_t)nnzb + 2560 + item_table_bytes(R);
+    // + 12 bytes per stored block: its block-row and the runs of the sampled product
+    size_t b = per_row * (size_t)R + 32 * (size_t)nnzb + 3072 + item_table_bytes(R);
     return (b + 255) & ~(size_t)255;
 }
 
@@ -341,6 +341,24 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
             for (int32_t p = index_pointer_host[r]; p < index_pointer_host[r + 1]; ++p) W->staging[at + (size_t)p] = (int32_t)r;
         W->block_row = W->row_order + at;
         words = (at + (size_t)nnzb + 63) & ~(size_t)63;
+        // runs of the sampled product: ceil(count / NB) runs per block-row, lengths differing by at most 1
+        const int NB = sddmm_run_blocks(bs_r, bs_c, dtype);
+        const size_t run_at = words;
+        W->staging.resize(run_at + 2 * (size_t)nnzb + 64, 0);
+        size_t q = 0;
+        for (int64_t r = 0; r < R; ++r) {
+            const int32_t first = index_pointer_host[r], cnt = index_pointer_host[r + 1] - first;
+            const int32_t parts = (cnt + NB - 1) / NB;
+            for (int32_t j = 0, p = first; j < parts; ++j, ++q) {
+                const int32_t len = cnt / parts + (j < cnt % parts ? 1 : 0);
+                W->staging[run_at + 2 * q] = p;
+                W->staging[run_at + 2 * q + 1] = len;
+                p += len;
+            }
+        }
+        W->sd_runs = W->row_order + run_at;
+        W->sd_n_runs = (int32_t)q;
+        words = (run_at + 2 * q + 63) & ~(size_t)63;
     }
     {   // the work-item table sits behind everything else, 256-byte aligned
         W->item_desc = const_cast<int32_t*>(W->row_order) + words;

@@ -74,6 +74,10 @@ struct bsr_matrix {
     // byte offsets of the tile's blocks in block_data, [entries][4] (2^31: no block there), and its
     // tile-column, [entries].
     const int32_t* block_row = nullptr;      // device, [nnzb]: block-row of every stored block (sampled product)
+    // Runs of the sampled product: every block-row cut into runs of at most sddmm_run_blocks() stored
+    // blocks of about equal length, in storage order; [sd_n_runs][2] = {first block, blocks}.
+    const int32_t* sd_runs = nullptr;
+    int32_t sd_n_runs = 0;
     const int32_t* sb_desc = nullptr;
     const int32_t* sb_entries = nullptr;
     const int32_t* sb_cols = nullptr;
@@ -104,6 +108,10 @@ struct spmm_args {
 };
 
 tune_opts read_tune_env();
+
+// Stored blocks of one block-row that a workgroup of the sampled product takes together (they share
+// the piece of G): 4 while a block is at most 2 KiB, else 2.
+inline int sddmm_run_blocks(int bs_r, int bs_c, bsr_dtype t) { return bs_r * bs_c * (t == BSR_F32 ? 4 : 2) <= 2048 ? 4 : 2; }
 
 // Each returns BSR_OK, BSR_ERR_UNSUPPORTED (shape not covered by that family) or BSR_ERR_HIP.
 bsr_status launch_wave(const spmm_args& a, const tune_opts& t);

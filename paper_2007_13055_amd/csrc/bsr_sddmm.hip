@@ -2,15 +2,17 @@
 // block p -- the gradient of the block values when Y = X * W^T is a layer's forward pass (Y is
 // linear in block_data[p][a][c] with coefficient X[i][col*bs_c + c] in Y[i][r*bs_r + a]).
 //
-// One workgroup (4 wavefronts) per stored block.  The reduction runs over the rows i of G and X,
-// which is the slow axis of both, so the operands cannot be read in MFMA order from memory.  A
-// wavefront takes every fourth chunk of 32 rows: it copies the 32 x bs_r piece of G and the
-// 32 x bs_c piece of X into its own LDS area with contiguous 16-byte reads (the next chunk's loads
-// are in flight while this one is multiplied), and reads the operands back transposed -- 16-bit
-// types with the LDS transpose read (ds_read_b64_tr_b16: each lane receives, for its row of the
-// MFMA operand, 4 consecutive values of the reduction index), fp32 one value per lane and MFMA
-// step.  Every wavefront accumulates the whole bs_r x bs_c block over its chunks; the four partial
-// blocks are added through LDS in fixed order and stored as one contiguous block.
+// One workgroup (4 wavefronts) per run of up to NB stored blocks of one block-row (the plan cuts
+// every block-row into runs of about equal length): the blocks of a run share the piece of G.  The
+// reduction runs over the rows i of G and X, which is the slow axis of both, so the operands cannot
+// be read in MFMA order from memory.  A wavefront takes every fourth chunk of 32 rows: it copies the
+// 32 x bs_r piece of G and the run's 32 x bs_c pieces of X into its own LDS area with contiguous
+// 16-byte reads (the next chunk's loads are in flight while this one is multiplied), and reads the
+// operands back transposed -- 16-bit types with the LDS transpose read (ds_read_b64_tr_b16: each
+// lane receives, for its row of the MFMA operand, 4 consecutive values of the reduction index),
+// fp32 one value per lane and MFMA step.  Every wavefront accumulates the run's whole blocks over
+// its chunks; the four partial blocks are added through LDS in fixed order and stored as one
+// contiguous block each.
 // Other block shapes: one thread per element of the block, a plain loop over i.
 #include <algorithm>
 
@@ -24,16 +26,17 @@ constexpr int kChunk = 32;                            // rows of G and X per ste
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
-template <typename T, int BS_R, int BS_C>
+template <typename T, int BS_R, int BS_C, int NB_>
 struct sddmm_geom {
     static constexpr int S = (int)sizeof(T);
+    static constexpr int NB = NB_;                                     // blocks per run
     static constexpr int MM = (BS_R >= 32 && BS_C >= 32) ? 32 : 16;   // MFMA tile edge
     static constexpr int NA = BS_R / MM, NC = BS_C / MM;
     static constexpr int RBG = BS_R * S, RBC = BS_C * S;               // bytes of a row of the G / X piece
     static constexpr int PG = RBG + 16, PC = RBC + 16;                 // padded LDS rows
     static constexpr int NLG = kChunk * RBG / 1024, NLX = kChunk * RBC / 1024;   // 1 KiB loads per chunk
     static constexpr int LDP = BS_C + 4;                               // padded row of the fp32 partial block
-    static constexpr int STAGE = kChunk * (PG + PC);
+    static constexpr int STAGE = kChunk * (PG + NB * PC);
     static constexpr int PART = BS_R * LDP * 4;
     static constexpr int REGION = ((STAGE > PART ? STAGE : PART) + 15) & ~15;
 };
@@ -66,14 +69,15 @@ __device__ __forceinline__ u32x4 read_operand16(const unsigned char* tile, int p
     return u32x4{a.x, a.y, b.x, b.y};
 }
 
-template <typename T, typename O, int BS_R, int BS_C>
+template <typename T, typename O, int BS_R, int BS_C, int NB_>
 __global__ __launch_bounds__(256) void bsr_sddmm_mfma(const T* __restrict__ G, const T* __restrict__ X,
                                                       const int32_t* __restrict__ block_row,
-                                                      const int32_t* __restrict__ indices, O* __restrict__ D,
-                                                      int m, int k, int n)
+                                                      const int32_t* __restrict__ indices,
+                                                      const int32_t* __restrict__ runs, O* __restrict__ D,
+                                                      int m, int k, int n, int n_runs)
 {
-    typedef sddmm_geom<T, BS_R, BS_C> geo;
-    constexpr int S = geo::S, MM = geo::MM, NA = geo::NA, NC = geo::NC;
+    typedef sddmm_geom<T, BS_R, BS_C, NB_> geo;
+    constexpr int S = geo::S, MM = geo::MM, NA = geo::NA, NC = geo::NC, NB = NB_;
     constexpr int RBG = geo::RBG, RBC = geo::RBC, PG = geo::PG, PC = geo::PC, NLG = geo::NLG, NLX = geo::NLX;
     constexpr int LDP = geo::LDP;
     static_assert(NLG >= 1 && NLX >= 1, "a chunk of either piece is at least one load per lane");
@@ -83,22 +87,33 @@ __global__ __launch_bounds__(256) void bsr_sddmm_mfma(const T* __restrict__ G, c
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int p = blockIdx.x;
-    const int r = block_row[p], c = indices[p];       // uniform: scalar reads
+    // workgroup b runs on XCD b mod 8: XCD x takes the x-th eighth of the runs, so that the pieces of G
+    // one XCD's L2 holds are those of consecutive block-rows
+    const int per_xcd = (int)gridDim.x / 8;
+    const int run = (int)(blockIdx.x % 8u) * per_xcd + (int)(blockIdx.x / 8u);
+    if (run >= n_runs) return;                        // whole workgroup: the grid is rounded up to 8
+    // uniform: scalar reads; 1 <= cnt <= NB.  Without a run table every stored block is its own run.
+    const int p0 = runs ? runs[2 * run] : run, cnt = runs ? runs[2 * run + 1] : 1;
+    const int r = block_row[p0];
     unsigned char* gt = lds + (size_t)wave * geo::REGION;     // G piece [kChunk][PG]
-    unsigned char* xt = gt + kChunk * PG;                     // X piece [kChunk][PC]
+    unsigned char* xt = gt + kChunk * PG;                     // X pieces [NB][kChunk][PC]
 
-    acc_t acc[NA][NC];
+    acc_t acc[NB][NA][NC];
 #pragma unroll
-    for (int ua = 0; ua < NA; ++ua)
+    for (int j = 0; j < NB; ++j)
 #pragma unroll
-        for (int uc = 0; uc < NC; ++uc)
+        for (int ua = 0; ua < NA; ++ua)
 #pragma unroll
-            for (int e = 0; e < NE; ++e) acc[ua][uc][e] = 0.f;
+            for (int uc = 0; uc < NC; ++uc)
+#pragma unroll
+                for (int e = 0; e < NE; ++e) acc[j][ua][uc][e] = 0.f;
 
     // lane's pieces of a chunk: piece t*64 + lane is 16 bytes of row (piece div pieces-per-row)
     const unsigned char* gbase = reinterpret_cast<const unsigned char*>(G + (size_t)r * BS_R);
-    const unsigned char* xbase = reinterpret_cast<const unsigned char*>(X + (size_t)c * BS_C);
+    const unsigned char* xbase[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+        xbase[j] = reinterpret_cast<const unsigned char*>(X + (size_t)indices[p0 + min(j, cnt - 1)] * BS_C);
     const size_t grow = (size_t)n * S, xrow = (size_t)k * S;
     int g_row[NLG], g_cb[NLG], x_row[NLX], x_cb[NLX];
 #pragma unroll
@@ -106,14 +121,19 @@ __global__ __launch_bounds__(256) void bsr_sddmm_mfma(const T* __restrict__ G, c
 #pragma unroll
     for (int t = 0; t < NLX; ++t) { const int q = t * 64 + lane; x_row[t] = q / (RBC / 16); x_cb[t] = (q % (RBC / 16)) * 16; }
 
-    u32x4 gg[NLG], gx[NLX];
+    // the branches on j < cnt are uniform over the workgroup
+    u32x4 gg[NLG], gx[NB][NLX];
     auto fetch = [&](int i0) {                        // rows past m repeat row m-1 and are zeroed when staged
 #pragma unroll
         for (int t = 0; t < NLG; ++t)
             gg[t] = *reinterpret_cast<const u32x4*>(gbase + (size_t)min(i0 + g_row[t], m - 1) * grow + g_cb[t]);
 #pragma unroll
-        for (int t = 0; t < NLX; ++t)
-            gx[t] = *reinterpret_cast<const u32x4*>(xbase + (size_t)min(i0 + x_row[t], m - 1) * xrow + x_cb[t]);
+        for (int j = 0; j < NB; ++j)
+            if (j < cnt) {
+#pragma unroll
+                for (int t = 0; t < NLX; ++t)
+                    gx[j][t] = *reinterpret_cast<const u32x4*>(xbase[j] + (size_t)min(i0 + x_row[t], m - 1) * xrow + x_cb[t]);
+            }
     };
     auto stage = [&](int i0) {
         const bool tail = i0 + kChunk > m;            // uniform
@@ -124,11 +144,15 @@ __global__ __launch_bounds__(256) void bsr_sddmm_mfma(const T* __restrict__ G, c
             *reinterpret_cast<u32x4*>(gt + g_row[t] * PG + g_cb[t]) = v;
         }
 #pragma unroll
-        for (int t = 0; t < NLX; ++t) {
-            u32x4 v = gx[t];
-            if (tail && i0 + x_row[t] >= m) v = u32x4{0u, 0u, 0u, 0u};
-            *reinterpret_cast<u32x4*>(xt + x_row[t] * PC + x_cb[t]) = v;
-        }
+        for (int j = 0; j < NB; ++j)
+            if (j < cnt) {
+#pragma unroll
+                for (int t = 0; t < NLX; ++t) {
+                    u32x4 v = gx[j][t];
+                    if (tail && i0 + x_row[t] >= m) v = u32x4{0u, 0u, 0u, 0u};
+                    *reinterpret_cast<u32x4*>(xt + j * (kChunk * PC) + x_row[t] * PC + x_cb[t]) = v;
+                }
+            }
     };
     auto compute = [&]() {
         if constexpr (std::is_same<T, float>::value) {
@@ -136,38 +160,49 @@ __global__ __launch_bounds__(256) void bsr_sddmm_mfma(const T* __restrict__ G, c
             const int irow = lane / MM, col = lane % MM;
 #pragma unroll
             for (int s = 0; s < kChunk / KS; ++s) {
-                float av[NA], bv[NC];
+                float av[NA];
 #pragma unroll
                 for (int ua = 0; ua < NA; ++ua) av[ua] = *reinterpret_cast<const float*>(gt + (s * KS + irow) * PG + (ua * MM + col) * 4);
 #pragma unroll
-                for (int uc = 0; uc < NC; ++uc) bv[uc] = *reinterpret_cast<const float*>(xt + (s * KS + irow) * PC + (uc * MM + col) * 4);
+                for (int j = 0; j < NB; ++j)
+                    if (j < cnt) {
+                        float bv[NC];
 #pragma unroll
-                for (int ua = 0; ua < NA; ++ua)
+                        for (int uc = 0; uc < NC; ++uc)
+                            bv[uc] = *reinterpret_cast<const float*>(xt + j * (kChunk * PC) + (s * KS + irow) * PC + (uc * MM + col) * 4);
 #pragma unroll
-                    for (int uc = 0; uc < NC; ++uc) {
-                        if constexpr (MM == 32) acc[ua][uc] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[ua], bv[uc], acc[ua][uc], 0, 0, 0);
-                        else                    acc[ua][uc] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ua], bv[uc], acc[ua][uc], 0, 0, 0);
+                        for (int ua = 0; ua < NA; ++ua)
+#pragma unroll
+                            for (int uc = 0; uc < NC; ++uc) {
+                                if constexpr (MM == 32) acc[j][ua][uc] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[ua], bv[uc], acc[j][ua][uc], 0, 0, 0);
+                                else                    acc[j][ua][uc] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ua], bv[uc], acc[j][ua][uc], 0, 0, 0);
+                            }
                     }
             }
         } else {
             constexpr int KI = MM == 32 ? 16 : 32;    // rows of the chunk one MFMA reduces over
 #pragma unroll
             for (int s = 0; s < kChunk / KI; ++s) {
-                Frag<T, 8> af[NA], bf[NC];
+                Frag<T, 8> af[NA];
 #pragma unroll
                 for (int ua = 0; ua < NA; ++ua) {
                     const u32x4 v = read_operand16<T, MM>(gt, PG, s * KI, ua * MM, lane);
                     af[ua].w[0] = v.x; af[ua].w[1] = v.y; af[ua].w[2] = v.z; af[ua].w[3] = v.w;
                 }
 #pragma unroll
-                for (int uc = 0; uc < NC; ++uc) {
-                    const u32x4 v = read_operand16<T, MM>(xt, PC, s * KI, uc * MM, lane);
-                    bf[uc].w[0] = v.x; bf[uc].w[1] = v.y; bf[uc].w[2] = v.z; bf[uc].w[3] = v.w;
-                }
+                for (int j = 0; j < NB; ++j)
+                    if (j < cnt) {
+                        Frag<T, 8> bf[NC];
 #pragma unroll
-                for (int ua = 0; ua < NA; ++ua)
+                        for (int uc = 0; uc < NC; ++uc) {
+                            const u32x4 v = read_operand16<T, MM>(xt + j * (kChunk * PC), PC, s * KI, uc * MM, lane);
+                            bf[uc].w[0] = v.x; bf[uc].w[1] = v.y; bf[uc].w[2] = v.z; bf[uc].w[3] = v.w;
+                        }
 #pragma unroll
-                    for (int uc = 0; uc < NC; ++uc) mfma_frag<T, MM, 8>(acc[ua][uc], af[ua], bf[uc]);
+                        for (int ua = 0; ua < NA; ++ua)
+#pragma unroll
+                            for (int uc = 0; uc < NC; ++uc) mfma_frag<T, MM, 8>(acc[j][ua][uc], af[ua], bf[uc]);
+                    }
             }
         }
     };
@@ -181,35 +216,102 @@ __global__ __launch_bounds__(256) void bsr_sddmm_mfma(const T* __restrict__ G, c
         compute();
     }
 
-    // partial block of this wavefront -> its LDS area as [bs_r][LDP] fp32 (the staged pieces are consumed:
-    // the wavefront's own LDS operations complete in order)
+    // One block of the run at a time: the wavefront's partial block -> its LDS area as [bs_r][LDP] fp32
+    // (the staged pieces are consumed: a wavefront's own LDS operations complete in order), then the
+    // fixed-order sum of the four partial blocks, 4 consecutive columns per thread, contiguous store.
     float* part = reinterpret_cast<float*>(gt);
 #pragma unroll
-    for (int ua = 0; ua < NA; ++ua)
+    for (int j = 0; j < NB; ++j) {
+        if (j >= cnt) break;
+        if (j > 0) __syncthreads();                   // the sums of block j-1 are read
 #pragma unroll
-        for (int uc = 0; uc < NC; ++uc)
+        for (int ua = 0; ua < NA; ++ua)
 #pragma unroll
-            for (int e = 0; e < NE; ++e) {
-                int a, cc;
-                if constexpr (MM == 32) { a = ua * 32 + 8 * (e / 4) + 4 * (lane / 32) + e % 4; cc = uc * 32 + lane % 32; }
-                else                    { a = ua * 16 + 4 * (lane / 16) + e;                    cc = uc * 16 + lane % 16; }
-                part[a * LDP + cc] = acc[ua][uc][e];
-            }
-    __syncthreads();
-
-    // fixed-order sum of the four partial blocks, 4 consecutive columns per thread, contiguous store
-    O* dst = D + (size_t)p * (BS_R * BS_C);
-    for (int e4 = threadIdx.x; e4 < BS_R * BS_C / 4; e4 += 256) {
-        const int a = (e4 * 4) / BS_C, cc = (e4 * 4) % BS_C;
-        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+            for (int uc = 0; uc < NC; ++uc)
 #pragma unroll
-        for (int w = 0; w < 4; ++w)
-            s += *reinterpret_cast<const f32x4*>(lds + (size_t)w * geo::REGION + ((size_t)a * LDP + cc) * 4);
-        store4<O>(dst + e4 * 4, s.x, s.y, s.z, s.w);
+                for (int e = 0; e < NE; ++e) {
+                    int a, cc;
+                    if constexpr (MM == 32) { a = ua * 32 + 8 * (e / 4) + 4 * (lane / 32) + e % 4; cc = uc * 32 + lane % 32; }
+                    else                    { a = ua * 16 + 4 * (lane / 16) + e;                    cc = uc * 16 + lane % 16; }
+                    part[a * LDP + cc] = acc[j][ua][uc][e];
+                }
+        __syncthreads();
+        O* dst = D + (size_t)(p0 + j) * (BS_R * BS_C);
+        for (int e4 = threadIdx.x; e4 < BS_R * BS_C / 4; e4 += 256) {
+            const int a = (e4 * 4) / BS_C, cc = (e4 * 4) % BS_C;
+            f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+                s += *reinterpret_cast<const f32x4*>(lds + (size_t)w * geo::REGION + ((size_t)a * LDP + cc) * 4);
+            store4<O>(dst + e4 * 4, s.x, s.y, s.z, s.w);
+        }
     }
 }
 
-// Any block shape: thread e of the workgroup owns elements e, e + 256, ... of the block.
+// Blocks below the MFMA tile with BS_R in {1, 2, 4, 8, 16} rows (any bs_c): a lane owns one column
+// of one stored block and keeps its BS_R sums.
+//   Workgroup (r, t): block-row r, lane slots 64t .. 64t+63 of its cnt*bs_c (block, column) pairs in
+//   storage order.  Its four wavefronts take the same slots and a quarter of the rows i each: per row
+//   a lane reads its one element of X (the slots of a block are adjacent elements), and the BS_R
+//   elements of G -- the same for the whole wavefront -- come through scalar registers.  The four
+//   partial sums are added through LDS in fixed order.
+// The reads of X are what bounds it: a wavefront instruction gathers 64 different columns of one row.
+template <typename T, typename O, int BS_R>
+__global__ __launch_bounds__(256) void bsr_sddmm_lanes(const T* __restrict__ G, const T* __restrict__ X,
+                                                       const int32_t* __restrict__ indptr,
+                                                       const int32_t* __restrict__ indices, O* __restrict__ D,
+                                                       int m, int k, int n, int bs_c)
+{
+    constexpr int kUnroll = 8;
+    __shared__ float part[4][BS_R][64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = blockIdx.x;
+    const int first = indptr[r], cnt = indptr[r + 1] - first;
+    const int slot0 = (int)blockIdx.y * 64;
+    if (slot0 >= cnt * bs_c) return;                  // whole workgroup
+    const int slot = slot0 + lane;
+    const bool live = slot < cnt * bs_c;
+    const int j = live ? slot / bs_c : 0, cc = live ? slot - j * bs_c : 0;
+    const int p = first + j;
+    const T* __restrict__ xcol = X + (size_t)indices[p] * bs_c + cc;
+    const T* __restrict__ gpiece = G + (size_t)r * BS_R;
+
+    float acc[BS_R];
+#pragma unroll
+    for (int a = 0; a < BS_R; ++a) acc[a] = 0.f;
+
+    const int per_wave = (m + 3) / 4;
+    const int i_begin = min(wave * per_wave, m), i_end = min(i_begin + per_wave, m);
+    int i = i_begin;
+    for (; i + kUnroll <= i_end; i += kUnroll) {
+        float xv[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) xv[u] = (float)xcol[(size_t)(i + u) * k];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const T* __restrict__ g = gpiece + (size_t)(i + u) * n;   // uniform address
+#pragma unroll
+            for (int a = 0; a < BS_R; ++a) acc[a] = fmaf((float)g[a], xv[u], acc[a]);
+        }
+    }
+    for (; i < i_end; ++i) {
+        const float x = (float)xcol[(size_t)i * k];
+        const T* __restrict__ g = gpiece + (size_t)i * n;
+#pragma unroll
+        for (int a = 0; a < BS_R; ++a) acc[a] = fmaf((float)g[a], x, acc[a]);
+    }
+#pragma unroll
+    for (int a = 0; a < BS_R; ++a) part[wave][a][lane] = acc[a];
+    __syncthreads();
+    if (!live) return;
+    for (int a = wave; a < BS_R; a += 4) {
+        const float sum = ((part[0][a][lane] + part[1][a][lane]) + part[2][a][lane]) + part[3][a][lane];
+        D[((size_t)p * BS_R + a) * bs_c + cc] = (O)sum;
+    }
+}
+
+// Any other block shape: thread e of the workgroup owns elements e, e + 256, ... of the block.
 template <typename T, typename O>
 __global__ __launch_bounds__(256) void bsr_sddmm_generic(const T* __restrict__ G, const T* __restrict__ X,
                                                          const int32_t* __restrict__ block_row,
@@ -228,18 +330,31 @@ __global__ __launch_bounds__(256) void bsr_sddmm_generic(const T* __restrict__ G
     }
 }
 
+template <typename T, typename O, int BS_R, int BS_C, int NB>
+bsr_status launch_sddmm_runs(const bsr_matrix* W, int m, const void* G, const void* X, void* D, const int32_t* runs,
+                             int n_runs, hipStream_t stream)
+{
+    typedef sddmm_geom<T, BS_R, BS_C, NB> geo;
+    const size_t lds = 4 * (size_t)geo::REGION;
+    static const hipError_t attr =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&bsr_sddmm_mfma<T, O, BS_R, BS_C, NB>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (attr != hipSuccess) return BSR_ERR_HIP;
+    hipLaunchKernelGGL((bsr_sddmm_mfma<T, O, BS_R, BS_C, NB>), dim3((unsigned)((n_runs + 7) / 8 * 8)), dim3(256), lds,
+                       stream, (const T*)G, (const T*)X, W->block_row, W->indices, runs, (O*)D, m, (int)W->k,
+                       (int)W->n, n_runs);
+    return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
+}
+
 template <typename T, typename O, int BS_R, int BS_C>
 bsr_status launch_sddmm_shape(const bsr_matrix* W, int m, const void* G, const void* X, void* D, hipStream_t stream)
 {
-    typedef sddmm_geom<T, BS_R, BS_C> geo;
-    const size_t lds = 4 * (size_t)geo::REGION;
-    static const hipError_t attr =
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&bsr_sddmm_mfma<T, O, BS_R, BS_C>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (attr != hipSuccess) return BSR_ERR_HIP;
-    hipLaunchKernelGGL((bsr_sddmm_mfma<T, O, BS_R, BS_C>), dim3((unsigned)W->nnzb), dim3(256), lds, stream,
-                       (const T*)G, (const T*)X, W->block_row, W->indices, (O*)D, m, (int)W->k, (int)W->n);
-    return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
+    constexpr int NB = BS_R * BS_C * (int)sizeof(T) <= 2048 ? 4 : 2;   // sddmm_run_blocks()
+    // Sharing the piece of G pays when the rows are many; a short product finishes sooner spread over
+    // more workgroups, one per stored block.
+    if (m >= 512 && W->sd_n_runs >= 256 && W->sd_runs && NB == sddmm_run_blocks(BS_R, BS_C, W->dtype))
+        return launch_sddmm_runs<T, O, BS_R, BS_C, NB>(W, m, G, X, D, W->sd_runs, W->sd_n_runs, stream);
+    return launch_sddmm_runs<T, O, BS_R, BS_C, 1>(W, m, G, X, D, nullptr, (int)W->nnzb, stream);
 }
 
 template <typename T, typename O>
@@ -247,6 +362,19 @@ bsr_status launch_sddmm_types(const bsr_matrix* W, int m, const void* G, const v
 {
     const int br = W->bs_r, bc = W->bs_c;
     BSR_MFMA_SHAPES(launch_sddmm_shape, T, O, br, bc, W, m, G, X, D, stream);
+    auto lanes = [&](auto rows_tag) -> bsr_status {
+        constexpr int BS_R = decltype(rows_tag)::value;
+        const int64_t tiles = ((int64_t)W->max_row_blocks * bc + 63) / 64;
+        if (tiles > 65535 || W->R > 0x7fffffff) return BSR_ERR_SHAPE;
+        hipLaunchKernelGGL((bsr_sddmm_lanes<T, O, BS_R>), dim3((unsigned)W->R, (unsigned)tiles), dim3(256), 0, stream,
+                           (const T*)G, (const T*)X, W->indptr, W->indices, (O*)D, m, (int)W->k, (int)W->n, bc);
+        return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
+    };
+    if (br == 16) return lanes(std::integral_constant<int, 16>{});
+    if (br == 8) return lanes(std::integral_constant<int, 8>{});
+    if (br == 4) return lanes(std::integral_constant<int, 4>{});
+    if (br == 2) return lanes(std::integral_constant<int, 2>{});
+    if (br == 1) return lanes(std::integral_constant<int, 1>{});
     hipLaunchKernelGGL((bsr_sddmm_generic<T, O>), dim3((unsigned)W->nnzb), dim3(256), 0, stream,
                        (const T*)G, (const T*)X, W->block_row, W->indices, (O*)D, m, (int)W->k, (int)W->n, br, bc);
     return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;

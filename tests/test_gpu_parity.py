@@ -486,7 +486,7 @@ def test_small_blocks_need_whole_tiles():
 
 
 @pytest.mark.parametrize("dtype,out", [("f32", "f32"), ("f16", "f16"), ("bf16", "bf16"), ("bf16", "f32")])
-@pytest.mark.parametrize("bs", SHAPES + [(8, 8), (16, 1), (3, 5)])
+@pytest.mark.parametrize("bs", SHAPES + [(8, 8), (16, 1), (1, 16), (4, 8), (2, 3), (8, 16), (3, 5)])
 def test_sampled_product_block_gradients(oracle_mod, dtype, out, bs):
     """D[p] = G[:, block-row]^T X[:, block-column] for every stored block, against the oracle: every matrix-core
     shape and three shapes of the plain loop; m below one chunk, one chunk per wavefront, a ragged tail, many."""
@@ -506,6 +506,48 @@ def test_sampled_product_block_gradients(oracle_mod, dtype, out, bs):
         torch.cuda.synchronize()
         check(D.double().cpu().numpy().reshape(p.nnzb, -1), Do.reshape(p.nnzb, -1), So.reshape(p.nnzb, -1), p.tau,
               f"sampled {bs} {dtype}->{out} m={m}", out_dtype=out)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("bs", [(16, 16), (32, 32), (64, 64), (16, 64), (8, 8), (16, 1), (1, 16), (16, 8)])
+def test_sampled_product_long_and_empty_rows(oracle_mod, dtype, bs):
+    """Block-rows longer than one run of blocks (and than 64 lane slots), next to empty ones."""
+    import torch
+    import paper_2007_13055_amd as lib
+    bs_r, bs_c = bs
+    counts = [37, 0, 5, 1, 0, 40, 9]
+    C, m = 40, 133
+    p = wl.make_problem("sdl", m, C * bs_c, len(counts) * bs_r, bs_r, bs_c, dtype, dtype, ("counts", counts), ("normal", 1.0),
+                        ("normal", 1.0), 1300 + bs_r + bs_c)
+    G = wl.round_to_storage(np.random.default_rng(5).normal(size=(m, p.n)).astype(np.float32), dtype)
+    Do, So = oracle_mod.bsr_sddmm(G, p.X, p.block_indices, p.index_pointer, bs_r, bs_c)
+    W = lib.bsr_create(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype=dtype)
+    D = lib.bsr_sddmm(W, to_device(G, dtype), to_device(p.X, dtype), d_dtype="f32")
+    torch.cuda.synchronize()
+    check(D.double().cpu().numpy().reshape(p.nnzb, -1), Do.reshape(p.nnzb, -1), So.reshape(p.nnzb, -1), p.tau,
+          f"sampled long rows {bs} {dtype}", out_dtype="f32")
+
+
+@pytest.mark.parametrize("bs,dtype", [((16, 16), "bf16"), ((16, 16), "f32"), ((32, 32), "f16"), ((32, 16), "f32"), ((64, 64), "f16")])
+def test_sampled_product_shared_runs(oracle_mod, bs, dtype):
+    """Many rows and many blocks: the stored blocks of a block-row are taken in runs that share the piece of G
+    (full runs, shorter ones, single blocks, empty block-rows), ragged last chunk of rows."""
+    import torch
+    import paper_2007_13055_amd as lib
+    bs_r, bs_c = bs
+    R, C, m = 90, 24, 531
+    counts = np.random.default_rng(9).integers(0, C + 1, size=R)
+    counts[:4] = [0, 1, C, 5]
+    assert sum((int(c) + 3) // 4 for c in counts) >= 256          # enough runs of 4 for the shared-run launch
+    p = wl.make_problem("sdr", m, C * bs_c, R * bs_r, bs_r, bs_c, dtype, dtype, ("counts", counts), ("normal", 1.0),
+                        ("normal", 1.0), 1400 + bs_r + bs_c)
+    G = wl.round_to_storage(np.random.default_rng(6).normal(size=(m, p.n)).astype(np.float32), dtype)
+    Do, So = oracle_mod.bsr_sddmm(G, p.X, p.block_indices, p.index_pointer, bs_r, bs_c)
+    W = lib.bsr_create(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype=dtype)
+    D = lib.bsr_sddmm(W, to_device(G, dtype), to_device(p.X, dtype), d_dtype="f32")
+    torch.cuda.synchronize()
+    check(D.double().cpu().numpy().reshape(p.nnzb, -1), Do.reshape(p.nnzb, -1), So.reshape(p.nnzb, -1), p.tau,
+          f"sampled runs {bs} {dtype}", out_dtype="f32")
 
 
 def test_sampled_product_small_integers_bitwise(oracle_mod):
