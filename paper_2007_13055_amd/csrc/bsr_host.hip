@@ -41,8 +41,8 @@ size_t plan_bytes(int64_t R, int64_t nnzb)
     // small blocks instead: tile-row descriptors (at most one per block-row) and 20 bytes per tile entry
     // (at most one per stored block)
     const size_t per_row = 4 + 8 * (size_t)kRowDescWords + 4 + 16 * (size_t)kStripeChunkPairs + 16;
-    // + 12 bytes per stored block: its block-row and the runs of the sampled product
-    size_t b = per_row * (size_t)R + 32 * (size_t)nnzb + 3072 + item_table_bytes(R);
+    // + 32 bytes per stored block for the sampled product: its block-row (4), runs (8), tiles (16 + 4)
+    size_t b = per_row * (size_t)R + 52 * (size_t)nnzb + 4096 + item_table_bytes(R);
     return (b + 255) & ~(size_t)255;
 }
 
@@ -359,6 +359,56 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
         W->sd_runs = W->row_order + run_at;
         W->sd_n_runs = (int32_t)q;
         words = (run_at + 2 * q + 63) & ~(size_t)63;
+        // tiles of the sampled product, for the shapes its matrix-core kernel takes: a stored block goes
+        // to the first tile of its (super-row, column group) whose position is free (a duplicate opens
+        // another tile); tiles of a super-row by column group, super-rows in order
+        int SR = 1, LC = 1;
+        sddmm_tile_dims(bs_r, bs_c, dtype, &SR, &LC);
+        const bool mfma_shape = (bs_r == 16 || bs_r == 32 || bs_r == 64) && (bs_c == 16 || bs_c == 32 || bs_c == 64);
+        if (mfma_shape && SR * LC > 1 && SR * LC <= 16) {
+            struct tile { int32_t cg; uint32_t mask; int32_t p[16]; };
+            const size_t tile_at = words;
+            W->staging.resize(tile_at + 5 * (size_t)nnzb + 128, 0);
+            std::vector<int32_t> plist;
+            plist.reserve((size_t)nnzb);
+            std::vector<tile> list;
+            size_t nt = 0;
+            for (int64_t sr = 0; sr * SR < R; ++sr) {
+                list.clear();
+                for (int a = 0; a < SR && sr * SR + a < R; ++a) {
+                    const int64_t r = sr * SR + a;
+                    for (int32_t p = index_pointer_host[r]; p < index_pointer_host[r + 1]; ++p) {
+                        const int32_t cg = block_indices_host[p] / LC, pos = a * LC + block_indices_host[p] % LC;
+                        tile* slot = nullptr;
+                        for (auto& t : list)
+                            if (t.cg == cg && !((t.mask >> pos) & 1u)) { slot = &t; break; }
+                        if (!slot) {
+                            list.push_back(tile{cg, 0u, {}});
+                            slot = &list.back();
+                        }
+                        slot->mask |= 1u << pos;
+                        slot->p[pos] = p;
+                    }
+                }
+                std::stable_sort(list.begin(), list.end(), [](const tile& x, const tile& y) { return x.cg < y.cg; });
+                for (const tile& t : list) {
+                    int32_t* d = W->staging.data() + tile_at + 4 * nt++;
+                    d[0] = (int32_t)sr;
+                    d[1] = t.cg;
+                    d[2] = (int32_t)plist.size();
+                    d[3] = (int32_t)t.mask;
+                    for (int pos = 0; pos < SR * LC; ++pos)
+                        if ((t.mask >> pos) & 1u) plist.push_back(t.p[pos]);
+                }
+            }
+            const size_t plist_at = (tile_at + 4 * nt + 63) & ~(size_t)63;
+            W->staging.resize(plist_at + plist.size() + 64, 0);
+            std::copy(plist.begin(), plist.end(), W->staging.begin() + (ptrdiff_t)plist_at);
+            W->sd_tiles = W->row_order + tile_at;
+            W->sd_plist = W->row_order + plist_at;
+            W->sd_n_tiles = (int32_t)nt;
+            words = (plist_at + plist.size() + 63) & ~(size_t)63;
+        }
     }
     {   // the work-item table sits behind everything else, 256-byte aligned
         W->item_desc = const_cast<int32_t*>(W->row_order) + words;

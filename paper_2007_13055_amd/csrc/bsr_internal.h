@@ -78,6 +78,12 @@ struct bsr_matrix {
     // blocks of about equal length, in storage order; [sd_n_runs][2] = {first block, blocks}.
     const int32_t* sd_runs = nullptr;
     int32_t sd_n_runs = 0;
+    // Tiles of the sampled product (block shapes whose pieces of G or X are narrower than 128 bytes, see
+    // sddmm_tile_dims): [sd_n_tiles][4] = {super-row, column group, first entry in sd_plist, position mask};
+    // sd_plist holds the stored-block numbers of a tile's set positions in position order.
+    const int32_t* sd_tiles = nullptr;
+    const int32_t* sd_plist = nullptr;
+    int32_t sd_n_tiles = 0;
     const int32_t* sb_desc = nullptr;
     const int32_t* sb_entries = nullptr;
     const int32_t* sb_cols = nullptr;
@@ -111,6 +117,14 @@ tune_opts read_tune_env();
 
 // Stored blocks of one block-row that a workgroup of the sampled product takes together (they share
 // the piece of G): 4 while a block is at most 2 KiB, else 2.
+// Tile of the sampled product: sr adjacent block-rows x lc adjacent block-columns, as many as make a
+// 128-byte line of a row of G and of X (1 when a block's piece is a line or more).
+inline void sddmm_tile_dims(int bs_r, int bs_c, bsr_dtype t, int* sr, int* lc)
+{
+    const int s = t == BSR_F32 ? 4 : 2;
+    *sr = bs_r * s >= 128 ? 1 : 128 / (bs_r * s);
+    *lc = bs_c * s >= 128 ? 1 : 128 / (bs_c * s);
+}
 inline int sddmm_run_blocks(int bs_r, int bs_c, bsr_dtype t) { return bs_r * bs_c * (t == BSR_F32 ? 4 : 2) <= 2048 ? 4 : 2; }
 
 // Each returns BSR_OK, BSR_ERR_UNSUPPORTED (shape not covered by that family) or BSR_ERR_HIP.

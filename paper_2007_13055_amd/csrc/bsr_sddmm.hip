@@ -248,6 +248,275 @@ __global__ __launch_bounds__(256) void bsr_sddmm_mfma(const T* __restrict__ G, c
     }
 }
 
+// Blocks whose pieces of G or X are narrower than a 128-byte line (16- and 32-wide blocks): a
+// workgroup per *tile* of SR adjacent block-rows x LC adjacent block-columns (SR*bs_r and LC*bs_c
+// elements fill a line), so every line that comes from L2 is used whole.  The plan lists the tiles
+// that hold a stored block: {super-row, column group, first entry of its block list, bit mask of the
+// SR*LC positions}; the block list holds the stored-block numbers of the set bits in position order.
+//
+// Moving a chunk global -> registers -> LDS -> registers costs three trips through the CU's memory
+// data path, which is what bounds this kernel; the loads therefore write LDS directly
+// (global_load_lds_dwordx4: lane l's 16 bytes land at the instruction's LDS base + 16*l, so a chunk
+// lies in LDS as rows without padding).  Which 16-byte piece of its row a lane fetches is free: the
+// pieces of row r are stored XOR-swizzled by sigma(r), which spreads the 4 rows a group of 16 lanes
+// reads together (and the rows of the neighbouring group) over different banks.  One buffer per
+// wavefront: wait for the chunk, read all its operands into registers, start the next chunk's
+// loads, multiply.  A position without a stored block is skipped (uniform branch on the mask).
+// Rows past m repeat row m-1 and are overwritten with zeros in LDS (last chunk only); columns past
+// n or k (a last, partial tile) are read from the tile's first column: absent positions only.
+template <typename T, int BS_R, int BS_C>
+struct sddmm_tile_geom {
+    static constexpr int S = (int)sizeof(T);
+    static constexpr int MM = (BS_R >= 32 && BS_C >= 32) ? 32 : 16;
+    static constexpr int NA = BS_R / MM, NC = BS_C / MM;
+    static constexpr int SR = BS_R * S >= 128 ? 1 : 128 / (BS_R * S);   // sddmm_tile_dims()
+    static constexpr int LC = BS_C * S >= 128 ? 1 : 128 / (BS_C * S);
+    static constexpr int NPOS = SR * LC;
+    static constexpr int RBG = SR * BS_R * S, RBC = LC * BS_C * S;      // bytes of a row of the G / X piece: 128 or 256
+    static constexpr int NLG = kChunk * RBG / 1024, NLX = kChunk * RBC / 1024;   // 1 KiB loads per chunk
+    static constexpr int LDP = BS_C + 4;
+    static constexpr int STAGE = kChunk * (RBG + RBC);
+    static constexpr int PART = BS_R * LDP * 4;                         // one partial block
+    static constexpr int PR = STAGE / PART >= 1 ? (STAGE / PART > NPOS ? NPOS : STAGE / PART) : 1;   // partial blocks per round
+    static constexpr int REGION = ((STAGE > PR * PART ? STAGE : PR * PART) + 1023) & ~1023;
+    static_assert(RBG == 128 || RBG == 256, "rows of the G piece");
+    static_assert(RBC == 128 || RBC == 256, "rows of the X piece");
+};
+
+// Byte offset of byte `cb` of row r in a chunk whose rows are RB bytes: 16-byte pieces XOR-swizzled.
+template <int RB>
+__device__ __forceinline__ int swz(int r, int cb)
+{
+    const int sigma = RB == 128 ? ((((r >> 1) & 1) << 1) | (((r >> 3) & 1) << 2))
+                                : (((r & 3) << 1) | (((r >> 3) & 1) << 3));
+    return r * RB + ((((cb >> 4) ^ sigma)) << 4) + (cb & 15);
+}
+
+// read_operand16 on a swizzled chunk (rows i0 .. of the chunk, element columns col0 ..).
+template <typename T, int MM, int RB>
+__device__ __forceinline__ u32x4 read_operand16_swz(const unsigned char* tile, int i0, int col0, int lane)
+{
+    const int lambda = lane & 15;
+    int irow, ccol;
+    if constexpr (MM == 32) {
+        irow = i0 + 8 * (lane >> 5) + (lambda >> 2);
+        ccol = col0 + 16 * ((lane >> 4) & 1) + 4 * (lambda & 3);
+    } else {
+        irow = i0 + 8 * (lane >> 4) + (lambda >> 2);
+        ccol = col0 + 4 * (lambda & 3);
+    }
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const unsigned char* p0 = tile + swz<RB>(irow, ccol * 2);       // row irow + 4 has the same sigma
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p0));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p0 + 4 * RB));
+    const u32x2 a = __builtin_bit_cast(u32x2, lo), b = __builtin_bit_cast(u32x2, hi);
+    return u32x4{a.x, a.y, b.x, b.y};
+}
+
+template <typename T, typename O, int BS_R, int BS_C>
+__global__ __launch_bounds__(256, sizeof(T) == 4 ? 3 : 4) void bsr_sddmm_tiles(const T* __restrict__ G, const T* __restrict__ X,
+                                                       const int32_t* __restrict__ tiles,
+                                                       const int32_t* __restrict__ plist, O* __restrict__ D,
+                                                       int m, int k, int n, int n_tiles)
+{
+    typedef sddmm_tile_geom<T, BS_R, BS_C> geo;
+    constexpr int S = geo::S, MM = geo::MM, NA = geo::NA, NC = geo::NC, SR = geo::SR, LC = geo::LC, NPOS = geo::NPOS;
+    constexpr int RBG = geo::RBG, RBC = geo::RBC, NLG = geo::NLG, NLX = geo::NLX;
+    constexpr int LDP = geo::LDP, PR = geo::PR;
+    typedef typename AccT<MM>::type acc_t;
+    constexpr int NE = MM == 32 ? 16 : 4;
+    typedef __attribute__((address_space(3))) void lds_void;
+    typedef __attribute__((address_space(1))) const void glob_void;
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];   // [4 wavefronts][REGION]
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int per_xcd = (int)gridDim.x / 8;           // XCD x takes the x-th eighth of the tiles
+    const int tile = (int)(blockIdx.x % 8u) * per_xcd + (int)(blockIdx.x / 8u);
+    if (tile >= n_tiles) return;                      // whole workgroup: the grid is rounded up to 8
+    const int sr = tiles[4 * tile], cg = tiles[4 * tile + 1], first = tiles[4 * tile + 2];   // uniform
+    const unsigned mask = (unsigned)tiles[4 * tile + 3];
+    unsigned char* gt = lds + (size_t)wave * geo::REGION;     // G piece [kChunk][RBG], swizzled
+    unsigned char* xt = gt + kChunk * RBG;                    // X piece [kChunk][RBC], swizzled
+
+    acc_t acc[NPOS][NA][NC];
+#pragma unroll
+    for (int q = 0; q < NPOS; ++q)
+#pragma unroll
+        for (int ua = 0; ua < NA; ++ua)
+#pragma unroll
+            for (int uc = 0; uc < NC; ++uc)
+#pragma unroll
+                for (int e = 0; e < NE; ++e) acc[q][ua][uc][e] = 0.f;
+
+    // load t of a piece fills LDS bytes [1024 t, 1024 t + 1024): lane l's slot is row (64 t + l) / (RB/16),
+    // stored piece (64 t + l) mod (RB/16), which holds the row's piece (stored piece ^ sigma(row))
+    const int gcol0 = sr * (SR * BS_R), xcol0 = cg * (LC * BS_C);   // first column of the pieces
+    const unsigned char* gbase = reinterpret_cast<const unsigned char*>(G + gcol0);
+    const unsigned char* xbase = reinterpret_cast<const unsigned char*>(X + xcol0);
+    const size_t grow = (size_t)n * S, xrow = (size_t)k * S;
+    int g_row[NLG], g_src[NLG], x_row[NLX], x_src[NLX];
+#pragma unroll
+    for (int t = 0; t < NLG; ++t) {
+        const int q = t * 64 + lane;
+        g_row[t] = q / (RBG / 16);
+        const int cb = (swz<RBG>(g_row[t], (q % (RBG / 16)) * 16) - g_row[t] * RBG);   // the piece this slot holds
+        g_src[t] = gcol0 + cb / S < n ? cb : 0;
+    }
+#pragma unroll
+    for (int t = 0; t < NLX; ++t) {
+        const int q = t * 64 + lane;
+        x_row[t] = q / (RBC / 16);
+        const int cb = (swz<RBC>(x_row[t], (q % (RBC / 16)) * 16) - x_row[t] * RBC);
+        x_src[t] = xcol0 + cb / S < k ? cb : 0;
+    }
+
+    auto fetch = [&](int i0) {                        // the wavefront's buffer must have been read out
+#pragma unroll
+        for (int t = 0; t < NLG; ++t)
+            __builtin_amdgcn_global_load_lds((glob_void*)(gbase + (size_t)min(i0 + g_row[t], m - 1) * grow + g_src[t]),
+                                             (lds_void*)(gt + 1024 * t), 16, 0, 0);
+#pragma unroll
+        for (int t = 0; t < NLX; ++t)
+            __builtin_amdgcn_global_load_lds((glob_void*)(xbase + (size_t)min(i0 + x_row[t], m - 1) * xrow + x_src[t]),
+                                             (lds_void*)(xt + 1024 * t), 16, 0, 0);
+    };
+    auto zero_tail = [&](int i0) {                    // rows past m of the last chunk: zeros in the lane's own slots
+#pragma unroll
+        for (int t = 0; t < NLG; ++t)
+            if (i0 + g_row[t] >= m) *reinterpret_cast<u32x4*>(gt + 1024 * t + 16 * lane) = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int t = 0; t < NLX; ++t)
+            if (i0 + x_row[t] >= m) *reinterpret_cast<u32x4*>(xt + 1024 * t + 16 * lane) = u32x4{0u, 0u, 0u, 0u};
+    };
+
+    const int n_chunks = (m + kChunk - 1) / kChunk;
+    if (wave < n_chunks) fetch(wave * kChunk);
+    for (int q = wave; q < n_chunks; q += 4) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // the chunk is in LDS
+        if ((q + 1) * kChunk > m) zero_tail(q * kChunk);          // uniform
+        const bool more = q + 4 < n_chunks;                        // uniform
+        if constexpr (std::is_same<T, float>::value) {
+            // fp32: one value per lane and MFMA step; the operands of half a chunk at a time, the next
+            // chunk's loads start once the second half is in registers
+            constexpr int KS = MM == 32 ? 2 : 4;      // reduction steps per MFMA
+            constexpr int STEPS = kChunk / KS, HALF = STEPS / 2;
+            const int irow = lane / MM, col = lane % MM;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                float av[HALF][SR][NA], bv[HALF][LC][NC];
+#pragma unroll
+                for (int s = 0; s < HALF; ++s) {
+                    const int r = (h * HALF + s) * KS + irow;
+#pragma unroll
+                    for (int a = 0; a < SR; ++a)
+#pragma unroll
+                        for (int ua = 0; ua < NA; ++ua)
+                            av[s][a][ua] = *reinterpret_cast<const float*>(gt + swz<RBG>(r, (a * BS_R + ua * MM + col) * 4));
+#pragma unroll
+                    for (int l = 0; l < LC; ++l)
+#pragma unroll
+                        for (int uc = 0; uc < NC; ++uc)
+                            bv[s][l][uc] = *reinterpret_cast<const float*>(xt + swz<RBC>(r, (l * BS_C + uc * MM + col) * 4));
+                }
+                if (h == 1) {
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // every read of the buffer has returned
+                    if (more) fetch((q + 4) * kChunk);
+                }
+#pragma unroll
+                for (int s = 0; s < HALF; ++s)
+#pragma unroll
+                    for (int pq = 0; pq < NPOS; ++pq)
+                        if ((mask >> pq) & 1u) {
+#pragma unroll
+                            for (int ua = 0; ua < NA; ++ua)
+#pragma unroll
+                                for (int uc = 0; uc < NC; ++uc) {
+                                    if constexpr (MM == 32) acc[pq][ua][uc] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s][pq / LC][ua], bv[s][pq % LC][uc], acc[pq][ua][uc], 0, 0, 0);
+                                    else                    acc[pq][ua][uc] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s][pq / LC][ua], bv[s][pq % LC][uc], acc[pq][ua][uc], 0, 0, 0);
+                                }
+                        }
+            }
+        } else {
+            constexpr int KI = MM == 32 ? 16 : 32;    // rows of the chunk one MFMA reduces over
+            constexpr int STEPS = kChunk / KI;
+            Frag<T, 8> af[STEPS][SR][NA], bf[STEPS][LC][NC];
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+#pragma unroll
+                for (int a = 0; a < SR; ++a)
+#pragma unroll
+                    for (int ua = 0; ua < NA; ++ua) {
+                        const u32x4 v = read_operand16_swz<T, MM, RBG>(gt, s * KI, a * BS_R + ua * MM, lane);
+                        af[s][a][ua].w[0] = v.x; af[s][a][ua].w[1] = v.y; af[s][a][ua].w[2] = v.z; af[s][a][ua].w[3] = v.w;
+                    }
+#pragma unroll
+                for (int l = 0; l < LC; ++l)
+#pragma unroll
+                    for (int uc = 0; uc < NC; ++uc) {
+                        const u32x4 v = read_operand16_swz<T, MM, RBC>(xt, s * KI, l * BS_C + uc * MM, lane);
+                        bf[s][l][uc].w[0] = v.x; bf[s][l][uc].w[1] = v.y; bf[s][l][uc].w[2] = v.z; bf[s][l][uc].w[3] = v.w;
+                    }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // every read of the buffer has returned
+            if (more) fetch((q + 4) * kChunk);
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s)
+#pragma unroll
+                for (int pq = 0; pq < NPOS; ++pq)
+                    if ((mask >> pq) & 1u) {
+#pragma unroll
+                        for (int ua = 0; ua < NA; ++ua)
+#pragma unroll
+                            for (int uc = 0; uc < NC; ++uc) mfma_frag<T, MM, 8>(acc[pq][ua][uc], af[s][pq / LC][ua], bf[s][pq % LC][uc]);
+                    }
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");              // nothing in flight into the buffer
+
+    // PR positions a round: partial blocks of the present ones -> the wavefront's LDS area, then the
+    // fixed-order sum over the four wavefronts and one contiguous store per block
+    float* part = reinterpret_cast<float*>(gt);
+    bool wrote = false;                               // uniform
+#pragma unroll
+    for (int q0 = 0; q0 < NPOS; q0 += PR) {
+        const unsigned round_mask = (mask >> q0) & ((1u << PR) - 1u);
+        if (round_mask == 0u) continue;
+        if (wrote) __syncthreads();                   // the sums of the round before are read
+        wrote = true;
+#pragma unroll
+        for (int j = 0; j < PR; ++j) {
+            if (q0 + j >= NPOS || !((round_mask >> j) & 1u)) continue;
+#pragma unroll
+            for (int ua = 0; ua < NA; ++ua)
+#pragma unroll
+                for (int uc = 0; uc < NC; ++uc)
+#pragma unroll
+                    for (int e = 0; e < NE; ++e) {
+                        int a, cc;
+                        if constexpr (MM == 32) { a = ua * 32 + 8 * (e / 4) + 4 * (lane / 32) + e % 4; cc = uc * 32 + lane % 32; }
+                        else                    { a = ua * 16 + 4 * (lane / 16) + e;                    cc = uc * 16 + lane % 16; }
+                        part[j * (BS_R * LDP) + a * LDP + cc] = acc[q0 + j < NPOS ? q0 + j : 0][ua][uc][e];
+                    }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < PR; ++j) {
+            if (q0 + j >= NPOS || !((round_mask >> j) & 1u)) continue;
+            const int p = plist[first + __builtin_popcount(mask & ((1u << (q0 + j)) - 1u))];
+            O* dst = D + (size_t)p * (BS_R * BS_C);
+            for (int e4 = threadIdx.x; e4 < BS_R * BS_C / 4; e4 += 256) {
+                const int a = (e4 * 4) / BS_C, cc = (e4 * 4) % BS_C;
+                f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int w = 0; w < 4; ++w)
+                    sum += *reinterpret_cast<const f32x4*>(lds + (size_t)w * geo::REGION + ((size_t)j * (BS_R * LDP) + (size_t)a * LDP + cc) * 4);
+                store4<O>(dst + e4 * 4, sum.x, sum.y, sum.z, sum.w);
+            }
+        }
+    }
+}
+
 // Blocks below the MFMA tile with BS_R in {1, 2, 4, 8, 16} rows (any bs_c): a lane owns one column
 // of one stored block and keeps its BS_R sums.
 //   Workgroup (r, t): block-row r, lane slots 64t .. 64t+63 of its cnt*bs_c (block, column) pairs in
@@ -347,8 +616,31 @@ bsr_status launch_sddmm_runs(const bsr_matrix* W, int m, const void* G, const vo
 }
 
 template <typename T, typename O, int BS_R, int BS_C>
+bsr_status launch_sddmm_tiles(const bsr_matrix* W, int m, const void* G, const void* X, void* D, hipStream_t stream)
+{
+    typedef sddmm_tile_geom<T, BS_R, BS_C> geo;
+    const size_t lds = 4 * (size_t)geo::REGION;
+    static const hipError_t attr =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&bsr_sddmm_tiles<T, O, BS_R, BS_C>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (attr != hipSuccess) return BSR_ERR_HIP;
+    hipLaunchKernelGGL((bsr_sddmm_tiles<T, O, BS_R, BS_C>), dim3((unsigned)((W->sd_n_tiles + 7) / 8 * 8)), dim3(256), lds,
+                       stream, (const T*)G, (const T*)X, W->sd_tiles, W->sd_plist, (O*)D, m, (int)W->k, (int)W->n,
+                       (int)W->sd_n_tiles);
+    return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
+}
+
+template <typename T, typename O, int BS_R, int BS_C>
 bsr_status launch_sddmm_shape(const bsr_matrix* W, int m, const void* G, const void* X, void* D, hipStream_t stream)
 {
+    // pieces narrower than a line, many rows, and enough tiles to fill the chip: line-wide tiles
+    if constexpr (sddmm_tile_geom<T, BS_R, BS_C>::NPOS > 1) {
+        int sr = 0, lc = 0;
+        sddmm_tile_dims(BS_R, BS_C, W->dtype, &sr, &lc);
+        if (m >= 512 && W->sd_n_tiles >= 256 && W->sd_tiles && sr == sddmm_tile_geom<T, BS_R, BS_C>::SR &&
+            lc == sddmm_tile_geom<T, BS_R, BS_C>::LC)
+            return launch_sddmm_tiles<T, O, BS_R, BS_C>(W, m, G, X, D, stream);
+    }
     constexpr int NB = BS_R * BS_C * (int)sizeof(T) <= 2048 ? 4 : 2;   // sddmm_run_blocks()
     // Sharing the piece of G pays when the rows are many; a short product finishes sooner spread over
     // more workgroups, one per stored block.

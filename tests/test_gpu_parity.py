@@ -550,6 +550,41 @@ def test_sampled_product_shared_runs(oracle_mod, bs, dtype):
           f"sampled runs {bs} {dtype}", out_dtype="f32")
 
 
+@pytest.mark.parametrize("bs,dtype,R,C", [((16, 16), "bf16", 70, 62), ((16, 16), "f32", 37, 35), ((32, 32), "f16", 45, 35),
+                                          ((16, 64), "f16", 70, 24), ((64, 16), "bf16", 20, 66), ((32, 16), "f32", 20, 35),
+                                          ((16, 32), "bf16", 70, 33)])
+def test_sampled_product_line_wide_tiles(oracle_mod, bs, dtype, R, C):
+    """Blocks whose pieces are narrower than a 128-byte line, many rows: workgroups take tiles of adjacent
+    block-rows x block-columns.  R and C leave a partial last tile in both directions; block-columns unsorted
+    inside the block-rows and one block stored twice (a second tile at the same place)."""
+    import torch
+    import paper_2007_13055_amd as lib
+    bs_r, bs_c = bs
+    m = 555
+    s = 4 if dtype == "f32" else 2
+    SR, LC = max(1, 128 // (bs_r * s)), max(1, 128 // (bs_c * s))
+    p = wl.make_problem("sdt", m, C * bs_c, R * bs_r, bs_r, bs_c, dtype, dtype, ("bernoulli", 0.5), ("normal", 1.0),
+                        ("normal", 1.0), 1500 + bs_r + bs_c)
+    rng = np.random.default_rng(12)
+    idx = p.block_indices.copy()
+    for r in range(R):
+        a, b = p.index_pointer[r], p.index_pointer[r + 1]
+        idx[a:b] = p.block_indices[rng.permutation(b - a) + a]
+    idx = np.concatenate([idx[:1], idx])                          # the first stored block twice
+    ptr = p.index_pointer.copy()
+    ptr[1:] += 1
+    rows = np.repeat(np.arange(R), np.diff(ptr))
+    assert len(set(zip((rows // SR).tolist(), (idx // LC).tolist()))) >= 256    # enough tiles for the tile launch
+    G = wl.round_to_storage(np.random.default_rng(8).normal(size=(m, p.n)).astype(np.float32), dtype)
+    Do, So = oracle_mod.bsr_sddmm(G, p.X, idx, ptr, bs_r, bs_c)
+    data = np.zeros((len(idx), bs_r, bs_c), dtype=p.block_data.dtype)
+    W = lib.bsr_create(p.n, p.k, data, idx, ptr, dtype=dtype)
+    D = lib.bsr_sddmm(W, to_device(G, dtype), to_device(p.X, dtype), d_dtype="f32")
+    torch.cuda.synchronize()
+    check(D.double().cpu().numpy().reshape(len(idx), -1), Do.reshape(len(idx), -1), So.reshape(len(idx), -1), p.tau,
+          f"sampled tiles {bs} {dtype}", out_dtype="f32")
+
+
 def test_sampled_product_small_integers_bitwise(oracle_mod):
     """Integer-valued G and X: every partial sum is exact in fp32, so the block gradients match bit for bit."""
     import torch
