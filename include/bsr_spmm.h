@@ -215,8 +215,11 @@ bsr_status bsr_transpose_values(bsr_dtype dtype, int32_t bs_r, int32_t bs_c, int
  *   G_dev   DEVICE, m*n elements of W's dtype, row-major     X_dev  DEVICE, m*k elements, row-major
  *   D_dev   DEVICE, nnzb*bs_r*bs_c elements of d_dtype (W's dtype or BSR_F32), the layout of
  *           block_data; every element is written; fp32 accumulation, rounded to nearest-even
- * Block shapes with bs_r, bs_c in {16, 32, 64} run on the matrix cores, any other shape on a plain
- * loop.  Asynchronous on hip_stream; reads W's pattern only, not its values.
+ * Block shapes with bs_r, bs_c in {16, 32, 64} run on the matrix cores; blocks of 1, 2, 4, 8 or 16
+ * rows and any width on a kernel that gives a lane one column of one block; any other shape on a plain
+ * loop.  Thin blocks (16 x 1, fp32) with scratch lent for this m (bsr_scratch_size, bsr_set_scratch): X is
+ * transposed into the scratch and a matrix-core kernel runs; the scratch is overwritten.
+ * Asynchronous on hip_stream; reads W's pattern only, not its values.
  * Errors: NULL, SHAPE (m < 0 or m*max(k,n) >= 2^31), DTYPE, ALIGN, HIP.
  */
 bsr_status bsr_sddmm(const bsr_matrix* W, int64_t m, const void* G_dev, const void* X_dev, void* D_dev,

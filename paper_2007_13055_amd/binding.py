@@ -272,15 +272,18 @@ def bsr_tune_result(W: BsrMatrix, m: int, y_dtype=None):
     return {**{k: int(v) for k, v in zip(keys, out)}, "us": float(us.value)}
 
 
-def bsr_sddmm(W: BsrMatrix, G, X, D=None, d_dtype=None):
+def bsr_sddmm(W: BsrMatrix, G, X, D=None, d_dtype=None, lend_scratch=True):
     """D[p] = G[:, block-row of p]^T @ X[:, block-column of p] for every stored block of W (the gradient
-    of the block values); G (m, n), X (m, k) device tensors of W's dtype.  Returns D (nnzb, bs_r, bs_c)."""
+    of the block values); G (m, n), X (m, k) device tensors of W's dtype.  Returns D (nnzb, bs_r, bs_c).
+    lend_scratch: lend the handle the scratch its thin-block kernel wants (as bsr_spmm does)."""
     import torch
     if G.dim() != 2 or X.dim() != 2 or G.shape[0] != X.shape[0] or G.shape[1] != W.n or X.shape[1] != W.k:
         raise ValueError("G must be (m, n) and X (m, k)")
     if _dtype_name(G) != W.dtype or _dtype_name(X) != W.dtype or not G.is_contiguous() or not X.is_contiguous():
         raise ValueError("G and X must be contiguous and of W's dtype")
     d_dtype = d_dtype or W.dtype
+    if lend_scratch:
+        W.ensure_scratch(int(G.shape[0]))
     nnzb = int(W.block_data.shape[0]) if W.block_data.dim() == 3 else 0
     if D is None:
         D = torch.empty((nnzb, W.bs_r, W.bs_c), dtype=_torch_dtype(d_dtype), device=G.device)

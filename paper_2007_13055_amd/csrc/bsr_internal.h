@@ -146,6 +146,8 @@ bool mfma_thin_supports(const bsr_matrix* W);
 bsr_status launch_mfma_small(const spmm_args& a, const tune_opts& t);   // bs_r, bs_c in {8,16}, not both 16
 bool mfma_small_supports(const bsr_matrix* W);
 size_t mfma_thin_scratch_bytes(const bsr_matrix* W, int64_t m);   // bytes of the transposed copy of X
+// XT[c][i] = X[i][c], rows of XT (m rounded up to 4) floats apart
+bsr_status launch_transpose_f32(const float* X, float* XT, int m, int k, hipStream_t stream);
 
 // Expands to a chain of `if (shape matches) return FN<T, O, BR, BC>(args...)` over the block
 // shapes the matrix-core kernels are instantiated for.

@@ -179,6 +179,13 @@ size_t mfma_thin_scratch_bytes(const bsr_matrix* W, int64_t m)
     return mfma_thin_supports(W) ? (((size_t)((m + 3) & ~(int64_t)3) * (size_t)W->k * sizeof(float) + 256 + 255) & ~(size_t)255) : 0;
 }
 
+bsr_status launch_transpose_f32(const float* X, float* XT, int m, int k, hipStream_t stream)
+{
+    if (m <= 0 || k <= 0) return BSR_OK;
+    hipLaunchKernelGGL(transpose_f32, dim3((k + 63) / 64, (m + 31) / 32), dim3(256), 0, stream, X, XT, m, k, (m + 3) & ~3);
+    return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
+}
+
 bsr_status launch_mfma_thin(const spmm_args& a, const tune_opts& tune)
 {
     const bsr_matrix* W = a.W;

@@ -580,6 +580,97 @@ __global__ __launch_bounds__(256) void bsr_sddmm_lanes(const T* __restrict__ G, 
     }
 }
 
+// Thin blocks (16 x 1, fp32) with a transposed copy XT (k x m) of X in the caller's scratch: a column of X
+// is then a contiguous row, and a block-row is a small dense product
+//     D[p0 .. p1)[a] = sum_i G[i][16 r + a] * XT[block column of p][i]
+// that the matrix cores take 16 stored blocks at a time: MFMA 16x16x4 with M = a, N = block, K = i.
+//   Workgroup (r, t): block-row r, its stored blocks 64 t .. 64 t + 63; wavefront w the 16 blocks from
+//   64 t + 16 w.  The rows i go by in pieces of 256: the workgroup copies that piece of G's 16 columns
+//   into LDS (64 contiguous bytes per row), every wavefront reads its 64 A operands from there (pitch
+//   20 words: the four row groups of a read fall on different banks), and then walks the piece 16 rows
+//   at a time: one 16-byte read of XT per lane (4 consecutive i of its block's column) feeds 4 MFMAs.
+//   MFMA u of a 16-row step reduces over i = I + 4 g + u for k-group g, on both operands.
+// Rows past m: G is read from row m-1 and replaced by zero, XT is read as it lies (the scratch is padded)
+// and replaced by zero; lanes past the block-row's last block repeat it and store nothing.
+__global__ __launch_bounds__(256, 4) void bsr_sddmm_thin16(const float* __restrict__ G, const float* __restrict__ XT,
+                                                        const int32_t* __restrict__ indptr,
+                                                        const int32_t* __restrict__ indices, float* __restrict__ D,
+                                                        int m, int n, int mp)
+{
+    constexpr int kPiece = 256, kPitch = 20;
+    __shared__ float gs[kPiece * kPitch];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = blockIdx.x;
+    const int first = indptr[r], cnt = indptr[r + 1] - first;
+    const int j0 = ((int)blockIdx.y * 4 + wave) * 16;             // first block of this wavefront's 16
+    if ((int)blockIdx.y * 64 >= cnt) return;                      // whole workgroup
+    const bool active = j0 < cnt;                                 // uniform over the wavefront
+    const int j = lane & 15, g = lane >> 4;
+    const int p = first + min(j0 + j, cnt - 1);
+    // XT is read with 4 consecutive lanes on the 64 contiguous bytes of one block's column (lane l: block
+    // l / 4, k-group l mod 4) and moved to the MFMA's lane order (block l mod 16, k-group l / 16) by lane
+    // permutes: four lanes of a quad on four different lines would quarter the load rate
+    const int jl = lane >> 2, gl = lane & 3;
+    const float* __restrict__ xrow = XT + (size_t)indices[first + min(j0 + jl, cnt - 1)] * mp + 4 * gl;
+    const int from = (4 * j + g) * 4;                             // byte address of the source lane for ds_bpermute
+    const float* __restrict__ gcols = G + (size_t)r * 16;
+
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acc2 = {0.f, 0.f, 0.f, 0.f};   // two chains: even and odd steps
+    for (int i0 = 0; i0 < m; i0 += kPiece) {
+        if (i0 > 0) __syncthreads();                              // the piece before is read
+        // rows i0 .. i0+255 of G's 16 columns -> LDS; thread t: rows t/4 + 64 q, 16 bytes at column 4 (t mod 4)
+#pragma unroll
+        for (int q = 0; q < kPiece / 64; ++q) {
+            const int row = (tid >> 2) + 64 * q;
+            const int i = i0 + row;
+            f32x4 v = *reinterpret_cast<const f32x4*>(gcols + (size_t)min(i, m - 1) * n + 4 * (tid & 3));
+            if (i >= m) v = f32x4{0.f, 0.f, 0.f, 0.f};
+            *reinterpret_cast<f32x4*>(gs + row * kPitch + 4 * (tid & 3)) = v;
+        }
+        __syncthreads();
+        if (!active) continue;
+        float A[kPiece / 16][4];
+#pragma unroll
+        for (int b = 0; b < kPiece / 16; ++b)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) A[b][u] = gs[(16 * b + 4 * g + u) * kPitch + j];
+        // the reads of XT of half a piece (8 steps) are issued before the first is used; a step past m
+        // repeats the last step's address and is not multiplied
+        const int last_step = ((m - 1) / 16) * 16;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            u32x4 xl[8];
+#pragma unroll
+            for (int b = 0; b < 8; ++b) xl[b] = *reinterpret_cast<const u32x4*>(xrow + min(i0 + 16 * (8 * h + b), last_step));
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                const int I = i0 + 16 * (8 * h + b);
+                if (I < m) {                                      // uniform
+                    f32x4 x;
+                    x.x = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(from, (int)xl[b].x));
+                    x.y = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(from, (int)xl[b].y));
+                    x.z = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(from, (int)xl[b].z));
+                    x.w = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(from, (int)xl[b].w));
+                    if (I + 16 > m) {                             // uniform: the last, partial step
+                        if (I + 4 * g + 0 >= m) x.x = 0.f;
+                        if (I + 4 * g + 1 >= m) x.y = 0.f;
+                        if (I + 4 * g + 2 >= m) x.z = 0.f;
+                        if (I + 4 * g + 3 >= m) x.w = 0.f;
+                    }
+                    f32x4& c = (b & 1) ? acc2 : acc;
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(A[8 * h + b][0], x.x, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(A[8 * h + b][1], x.y, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(A[8 * h + b][2], x.z, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(A[8 * h + b][3], x.w, c, 0, 0, 0);
+                }
+            }
+        }
+    }
+    // lane (block j, group g) holds D[p][4 g .. 4 g + 3]
+    if (active && j0 + j < cnt) *reinterpret_cast<f32x4*>(D + (size_t)p * 16 + 4 * g) = acc + acc2;
+}
+
 // Any other block shape: thread e of the workgroup owns elements e, e + 256, ... of the block.
 template <typename T, typename O>
 __global__ __launch_bounds__(256) void bsr_sddmm_generic(const T* __restrict__ G, const T* __restrict__ X,
@@ -654,6 +745,21 @@ bsr_status launch_sddmm_types(const bsr_matrix* W, int m, const void* G, const v
 {
     const int br = W->bs_r, bc = W->bs_c;
     BSR_MFMA_SHAPES(launch_sddmm_shape, T, O, br, bc, W, m, G, X, D, stream);
+    if constexpr (std::is_same<T, float>::value && std::is_same<O, float>::value) {
+        // thin blocks with the caller's scratch lent: transposed copy of X, then the matrix-core kernel
+        if (mfma_thin_supports(W) && m >= 32 && W->scratch && W->scratch_bytes >= mfma_thin_scratch_bytes(W, m) &&
+            ((int64_t)m + 3) * W->k < ((int64_t)1 << 30)) {
+            float* XT = static_cast<float*>(W->scratch);
+            const bsr_status st = launch_transpose_f32((const float*)X, XT, m, (int)W->k, stream);
+            if (st != BSR_OK) return st;
+            const int64_t groups = ((int64_t)W->max_row_blocks + 63) / 64;
+            if (groups > 65535) return BSR_ERR_SHAPE;
+            hipLaunchKernelGGL(bsr_sddmm_thin16, dim3((unsigned)W->R, (unsigned)groups), dim3(256), 0, stream,
+                               (const float*)G, (const float*)XT, W->indptr, W->indices, (float*)D, m, (int)W->n,
+                               (m + 3) & ~3);
+            return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
+        }
+    }
     auto lanes = [&](auto rows_tag) -> bsr_status {
         constexpr int BS_R = decltype(rows_tag)::value;
         const int64_t tiles = ((int64_t)W->max_row_blocks * bc + 63) / 64;

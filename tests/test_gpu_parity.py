@@ -585,6 +585,28 @@ def test_sampled_product_line_wide_tiles(oracle_mod, bs, dtype, R, C):
           f"sampled tiles {bs} {dtype}", out_dtype="f32")
 
 
+@pytest.mark.parametrize("lend", [True, False])
+@pytest.mark.parametrize("m", [32, 45, 256, 300, 777])
+def test_sampled_product_thin_blocks(oracle_mod, m, lend):
+    """16x1 fp32 blocks: with scratch lent, a transposed copy of X and the matrix-core kernel (rows of X in
+    pieces of 256, partial last piece and step; block-rows of more than 64 blocks, of 16 k + 1, and empty);
+    without, the lane-per-column kernel.  Same results to tolerance."""
+    import torch
+    import paper_2007_13055_amd as lib
+    counts = [70, 0, 17, 1, 16, 64, 65, 33]
+    C = 80
+    p = wl.make_problem("sdthin", m, C, len(counts) * 16, 16, 1, "f32", "f32", ("counts", counts), ("uniform", 1.0),
+                        ("uniform", 1.0), 1600 + m)
+    G = np.random.default_rng(m).normal(size=(m, p.n)).astype(np.float32)
+    Do, So = oracle_mod.bsr_sddmm(G, p.X, p.block_indices, p.index_pointer, 16, 1)
+    W = lib.bsr_create(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype="f32")
+    D = torch.full((p.nnzb, 16, 1), float("nan"), device="cuda")
+    lib.bsr_sddmm(W, to_device(G, "f32"), to_device(p.X, "f32"), D, d_dtype="f32", lend_scratch=lend)
+    torch.cuda.synchronize()
+    check(D.double().cpu().numpy().reshape(p.nnzb, -1), Do.reshape(p.nnzb, -1), So.reshape(p.nnzb, -1), p.tau,
+          f"sampled thin m={m} scratch={lend}", out_dtype="f32")
+
+
 def test_sampled_product_small_integers_bitwise(oracle_mod):
     """Integer-valued G and X: every partial sum is exact in fp32, so the block gradients match bit for bit."""
     import torch
