@@ -14,27 +14,37 @@
 
 namespace {
 
-// t_data[q][c][a] = data[perm[q]][a][c].  One workgroup per stored block; a bs_r x bs_c block is at
-// most 64 x 64 elements here, staged through LDS so that both the read and the write run along
-// the contiguous index.  Larger blocks (or odd shapes) take the plain strided loop.
+// t_data[q][c][a] = data[perm[q]][a][c].  A workgroup takes `per` stored blocks (one when a block has
+// more than 128 elements, else as many as its 256 threads cover); a bs_r x bs_c block is at most
+// 64 x 64 elements here, staged through LDS so that both the read and the write run along the
+// contiguous index.
 template <typename T>
 __global__ __launch_bounds__(256) void transpose_blocks(const T* __restrict__ data, const int32_t* __restrict__ perm,
-                                                        T* __restrict__ t_data, int bs_r, int bs_c)
+                                                        T* __restrict__ t_data, int bs_r, int bs_c, int per, int nnzb)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char raw[];
-    T* tile = reinterpret_cast<T*>(raw);              // [bs_r][bs_c + 1]
-    const int q = blockIdx.x;
-    const T* src = data + (size_t)perm[q] * bs_r * bs_c;
-    T* dst = t_data + (size_t)q * bs_r * bs_c;
+    T* tiles = reinterpret_cast<T*>(raw);             // [per][bs_r][bs_c + 1]
     const int elems = bs_r * bs_c, pitch = bs_c + 1;
-    for (int e = threadIdx.x; e < elems; e += blockDim.x) {
-        const int a = e / bs_c, c = e - a * bs_c;
-        tile[a * pitch + c] = src[e];
+    // thread -> (block of the workgroup, first element): threads_per_block threads stride over a block
+    const int tpb = 256 / per;
+    const int lb = (int)threadIdx.x / tpb, t = (int)threadIdx.x - lb * tpb;
+    const int q = (int)blockIdx.x * per + lb;
+    const bool live = lb < per && q < nnzb;
+    T* tile = tiles + (size_t)lb * bs_r * pitch;
+    if (live) {
+        const T* src = data + (size_t)perm[q] * elems;
+        for (int e = t; e < elems; e += tpb) {
+            const int a = e / bs_c, c = e - a * bs_c;
+            tile[a * pitch + c] = src[e];
+        }
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < elems; e += blockDim.x) {
-        const int c = e / bs_r, a = e - c * bs_r;
-        dst[e] = tile[a * pitch + c];
+    if (live) {
+        T* dst = t_data + (size_t)q * elems;
+        for (int e = t; e < elems; e += tpb) {
+            const int c = e / bs_r, a = e - c * bs_r;
+            dst[e] = tile[a * pitch + c];
+        }
     }
 }
 
@@ -73,15 +83,20 @@ bsr_status bsr_transpose_values(bsr_dtype dtype, int32_t bs_r, int32_t bs_c, int
     if (nnzb == 0) return BSR_OK;
     if (!perm_dev || !block_data_dev || !t_block_data_dev) return BSR_ERR_NULL;
     const size_t es = dtype == BSR_F32 ? 4 : 2;
-    const size_t lds = (size_t)bs_r * (size_t)(bs_c + 1) * es;
+    const int elems = bs_r * bs_c;
+    const int per = elems > 128 ? 1 : 256 / elems;        // stored blocks per workgroup
+    const size_t lds = (size_t)per * (size_t)bs_r * (size_t)(bs_c + 1) * es;
     if (lds > 64 * 1024) return BSR_ERR_UNSUPPORTED;      // blocks beyond 64 KiB are not staged
+    const unsigned grid = (unsigned)((nnzb + per - 1) / per);
     hipStream_t stream = (hipStream_t)hip_stream;
     if (es == 4)
-        hipLaunchKernelGGL(transpose_blocks<uint32_t>, dim3((unsigned)nnzb), dim3(256), lds, stream,
-                           (const uint32_t*)block_data_dev, perm_dev, (uint32_t*)t_block_data_dev, bs_r, bs_c);
+        hipLaunchKernelGGL(transpose_blocks<uint32_t>, dim3(grid), dim3(256), lds, stream,
+                           (const uint32_t*)block_data_dev, perm_dev, (uint32_t*)t_block_data_dev, bs_r, bs_c, per,
+                           (int)nnzb);
     else
-        hipLaunchKernelGGL(transpose_blocks<uint16_t>, dim3((unsigned)nnzb), dim3(256), lds, stream,
-                           (const uint16_t*)block_data_dev, perm_dev, (uint16_t*)t_block_data_dev, bs_r, bs_c);
+        hipLaunchKernelGGL(transpose_blocks<uint16_t>, dim3(grid), dim3(256), lds, stream,
+                           (const uint16_t*)block_data_dev, perm_dev, (uint16_t*)t_block_data_dev, bs_r, bs_c, per,
+                           (int)nnzb);
     return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
 }
 

@@ -407,7 +407,8 @@ def test_tuned_product_matches_oracle(oracle_mod, case):
 
 
 @pytest.mark.parametrize("case", [("f32", 32, 32, 128, 10, 12), ("bf16", 16, 16, 300, 20, 12), ("f16", 64, 32, 70, 5, 9),
-                                  ("f32", 16, 1, 40, 6, 50), ("f32", 8, 4, 8, 10, 16), ("f16", 16, 64, 1, 7, 3)])
+                                  ("f32", 16, 1, 40, 6, 50), ("f32", 8, 4, 8, 10, 16), ("f16", 16, 64, 1, 7, 3),
+                                  ("f32", 3, 5, 9, 7, 11), ("bf16", 8, 16, 33, 9, 13)])
 def test_sibling_product_through_transposed_handle(oracle_mod, case):
     """Z = G * W as bsr_spmm on the handle of W^T (bsr_transpose_pattern + bsr_transpose_values), against
     the oracle's own sibling product; and the transposed values are exactly W's, block by block."""
