@@ -414,6 +414,8 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
         W->item_desc = const_cast<int32_t*>(W->row_order) + words;
         W->item_capacity = item_table_bytes(R) / (kRowDescWords * sizeof(int32_t));
     }
+    // the plan must fit what bsr_workspace_size promised (its bound is per block-row and per stored block)
+    if (sizeof(int32_t) * words + item_table_bytes(R) > workspace_bytes) { delete W; return BSR_ERR_WORKSPACE; }
     if (R > 0) {
         hipError_t e = hipMemcpyAsync(workspace_dev, W->staging.data(), sizeof(int32_t) * words,
                                       hipMemcpyHostToDevice, (hipStream_t)hip_stream);

@@ -90,3 +90,47 @@ def test_transpose_pattern_against_scipy(lib):
     assert t_ptr2.tolist() == [0, 1, 4] and t_idx2.tolist() == [0, 0, 0, 1] and perm2.tolist() == [1, 0, 2, 3]
     with pytest.raises(lib.BsrError):
         lib.bsr_transpose_pattern(8, 8, 4, 4, [0, 1, 1], [5])          # column out of range
+
+
+@pytest.mark.parametrize("bs_r,bs_c,dtype", [(16, 16, "bf16"), (16, 16, "f32"), (8, 8, "f32"), (8, 16, "f16"), (32, 32, "f16"),
+                                              (64, 64, "f16"), (16, 64, "bf16"), (16, 1, "f32"), (3, 5, "f32")])
+@pytest.mark.parametrize("pattern", ["one_per_row", "duplicates", "full", "one_long_row"])
+def test_plan_fits_the_promised_workspace(lib, bs_r, bs_c, dtype, pattern):
+    """bsr_create builds its whole plan (row descriptors, pair / tile / run tables) on the host before the
+    upload and refuses a workspace that is too small: with exactly bsr_workspace_size() bytes it must never
+    answer WORKSPACE, whatever the pattern.  No GPU: the upload then fails with HIP, which is fine here."""
+    R, C = 37, 41
+    if pattern == "one_per_row":
+        counts = [1] * R
+        idx = [(7 * r) % C for r in range(R)]
+    elif pattern == "duplicates":
+        counts = [6] * R
+        idx = [c for r in range(R) for c in (r % C, r % C, r % C, (r + 5) % C, (r + 5) % C, (r + 9) % C)]
+    elif pattern == "full":
+        counts = [C] * R
+        idx = list(range(C)) * R
+    else:
+        counts = [0] * R
+        counts[5] = C
+        idx = list(range(C))
+    ptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    idx = np.asarray(idx, dtype=np.int32)
+    nnzb = int(idx.shape[0])
+    n, k = R * bs_r, C * bs_c
+    so = lib.load_library()
+    need = lib.bsr_workspace_size(n, k, bs_r, bs_c, nnzb)
+    es = 4 if dtype == "f32" else 2
+    data = np.zeros(nnzb * bs_r * bs_c * es + 64, dtype=np.uint8)       # stand-ins for device buffers: never read here
+    ws = np.zeros(need + 64, dtype=np.uint8)
+    align = lambda a: (a.ctypes.data + 15) & ~15
+    handle = ctypes.c_void_p()
+    code = {"f32": 0, "f16": 1, "bf16": 2}[dtype]
+    st = so.bsr_create(ctypes.byref(handle), n, k, bs_r, bs_c, nnzb, code, align(data), idx.ctypes.data, ptr.ctypes.data,
+                       idx.ctypes.data, ptr.ctypes.data, align(ws), need, None)
+    assert st in (0, 8), lib.bsr_status_string(st)                      # OK (a GPU is present) or HIP (none): never WORKSPACE
+    if st == 0:
+        so.bsr_destroy(handle)
+    # one byte less is refused before anything is built
+    st = so.bsr_create(ctypes.byref(handle), n, k, bs_r, bs_c, nnzb, code, align(data), idx.ctypes.data, ptr.ctypes.data,
+                       idx.ctypes.data, ptr.ctypes.data, align(ws), need - 256, None)
+    assert st == 7
