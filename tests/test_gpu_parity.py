@@ -111,6 +111,65 @@ def test_config5_full_size_sampled_rows(oracle_mod):
     assert np.array_equal(wl.round_to_storage(Yg32.astype(np.float32), "f16").astype(np.float64), Yg)
 
 
+# ------------------------------------------------------------------ the sibling products at full size
+def _gradient_like(p, seed):
+    """A seeded G (m, n) of the workload's input type: what a layer's backward pass hands to the siblings."""
+    g = np.random.default_rng(seed).normal(size=(p.m, p.n)).astype(np.float32)
+    return wl.round_to_storage(g, p.in_dtype)
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
+def test_config_full_size_sampled_product(oracle_mod, cid):
+    """D = (G^T X) at the stored blocks on the five configurations at full size, launched as bench.py
+    launches it.  The GPU computes every block; the oracle every block (1-4) or, for configuration 5, a
+    sample of blocks: first, last, some of the longest block-row, a seeded random set."""
+    import torch
+    import paper_2007_13055_amd as lib
+    p = wl.config(cid)
+    G = _gradient_like(p, 900 + cid)
+    W = lib.bsr_create(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype=p.in_dtype)
+    Gd, Xd = to_device(G, p.in_dtype), to_device(p.X, p.in_dtype)
+    D = lib.bsr_sddmm(W, Gd, Xd, d_dtype=p.out_dtype)
+    D32 = lib.bsr_sddmm(W, Gd, Xd, d_dtype="f32")
+    torch.cuda.synchronize()
+    if cid < 5:
+        pick = np.arange(p.nnzb)
+        idx, ptr = p.block_indices, p.index_pointer
+    else:
+        counts = np.diff(p.index_pointer)
+        longest = int(np.argmax(counts))
+        a = int(p.index_pointer[longest])
+        pick = np.unique(np.concatenate([[0, p.nnzb - 1], a + np.array([0, 1, 2, 63, 64, int(counts[longest]) - 1]),
+                                         np.random.default_rng(5).integers(0, p.nnzb, size=40)]))
+        rows = np.repeat(np.arange(p.n // p.bs_r), counts)[pick]
+        idx = p.block_indices[pick]
+        ptr = np.concatenate([[0], np.cumsum(np.bincount(rows, minlength=p.n // p.bs_r))]).astype(np.int32)
+    Do, So = oracle_mod.bsr_sddmm(G, p.X, idx, ptr, p.bs_r, p.bs_c)
+    sel = torch.as_tensor(pick, device="cuda")
+    flat = lambda t: t[sel].double().cpu().numpy().reshape(len(pick), -1)
+    check(flat(D32), Do.reshape(len(pick), -1), So.reshape(len(pick), -1), p.tau, f"config {cid} sampled product, fp32 output")
+    check(flat(D), Do.reshape(len(pick), -1), So.reshape(len(pick), -1), p.tau, f"config {cid} sampled product",
+          out_dtype=p.out_dtype)
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
+def test_config_full_size_transposed_sibling(oracle_mod, cid):
+    """Z = G * W through the handle of W^T on the five configurations at full size; configuration 5 against
+    the oracle on sampled rows of G (a row of Z depends on that row of G only)."""
+    import torch
+    import paper_2007_13055_amd as lib
+    p = wl.config(cid)
+    G = _gradient_like(p, 950 + cid)
+    WT = lib.bsr_create_transposed(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype=p.in_dtype)
+    Z = lib.bsr_spmm(WT, to_device(G, p.in_dtype), y_dtype=p.out_dtype)
+    torch.cuda.synchronize()
+    rows = np.arange(p.m) if cid < 5 else np.unique(np.concatenate(
+        [[0, 1, 127, 128, 4095, 4096, p.m - 1], np.random.default_rng(6).integers(0, p.m, size=40)]))
+    Zo, So = oracle_mod.bsr_spmm_w(G[rows], p.block_data, p.block_indices, p.index_pointer, p.k)
+    Zg = Z[torch.as_tensor(rows, device="cuda")].double().cpu().numpy()
+    check(Zg, Zo, So, p.tau, f"config {cid} transposed sibling", out_dtype=p.out_dtype)
+
+
 # ------------------------------------------------------------------ exact cases
 @pytest.mark.parametrize("path", [WAVE, MFMA])
 @pytest.mark.parametrize("dtype,out", [("f32", "f32"), ("f16", "f32"), ("bf16", "f32"), ("f16", "f16")])
