@@ -300,6 +300,38 @@ def test_degenerate_sizes_and_errors():
     assert e.value.status == 6
 
 
+def test_sampled_product_degenerate_sizes_and_errors():
+    """bsr_sddmm's documented codes: nothing stored, m = 0 (an empty sum: zeros), NULL, negative m, an output
+    type that is neither the input type nor fp32, a misaligned pointer."""
+    import torch
+    import paper_2007_13055_amd as lib
+    so = lib.load_library()
+    stream = torch.cuda.current_stream().cuda_stream
+    W0 = lib.bsr_create(32, 32, np.zeros((0, 16, 16), np.float32), [], [0, 0, 0])
+    G, X = torch.ones((5, 32), device="cuda"), torch.ones((5, 32), device="cuda")
+    assert tuple(lib.bsr_sddmm(W0, G, X).shape) == (0, 16, 16)
+    for bs in ((16, 16), (16, 1), (3, 5)):                            # matrix-core, lane-per-column, plain loop
+        p = wl.make_problem("t", 4, 6 * bs[1], 5 * bs[0], bs[0], bs[1], "f32", "f32", ("bernoulli", 0.6), ("normal", 1),
+                            ("normal", 1), 2)
+        W = lib.bsr_create(p.n, p.k, p.block_data, p.block_indices, p.index_pointer)
+        D = torch.full((p.nnzb, bs[0], bs[1]), float("nan"), device="cuda")
+        lib.bsr_sddmm(W, torch.ones((0, p.n), device="cuda"), torch.ones((0, p.k), device="cuda"), D)
+        torch.cuda.synchronize()
+        assert torch.all(D == 0), bs                                  # m = 0: every element written, an empty sum
+    G, X = to_device(np.ones((4, p.n), np.float32), "f32"), to_device(p.X, "f32")
+    D = torch.empty((p.nnzb, 3, 5), device="cuda")
+    args = lambda **kw: [kw.get("W", W.handle), kw.get("m", 4), kw.get("G", G.data_ptr()), kw.get("X", X.data_ptr()),
+                         kw.get("D", D.data_ptr()), kw.get("t", 0), stream]
+    assert so.bsr_sddmm(*args()) == 0
+    assert so.bsr_sddmm(*args(W=None)) == 1                           # NULL handle
+    assert so.bsr_sddmm(*args(D=None)) == 1
+    assert so.bsr_sddmm(*args(G=None)) == 1
+    assert so.bsr_sddmm(*args(m=-1)) == 2
+    assert so.bsr_sddmm(*args(t=1)) == 5                              # fp16 output of an fp32 W
+    assert so.bsr_sddmm(*args(X=X.data_ptr() + 4)) == 6
+    torch.cuda.synchronize()
+
+
 def test_repeat_calls_are_bitwise_identical(oracle_mod):
     """No atomics in the default plan: two runs must agree bit for bit (catches races)."""
     p = wl.config(2)
