@@ -129,7 +129,17 @@ def _bench_config(cid, steps, warmup, graph_chunk):
     wall, ev, mode = _time_steps(fn, steps, warmup, graph_chunk)
     eager_wall, _, _ = _time_steps(fn, steps, 0, 0)
     return p, W, {"wall_s": wall, "event_s": ev, "mode": mode, "eager_wall_s": eager_wall,
-                  "path": {1: "wave", 2: "mfma"}[lib.bsr_query_path(W, p.m)]}
+                  "path": {1: "wave", 2: "mfma"}[lib.bsr_query_path(W, p.m)], "X": X, "Y": Y}
+
+
+def _spread(p, W, X, Y, steps, graph_chunk, repeats=10):
+    """Run-to-run spread of the time per product: `repeats` further timed regions of `steps` launches each
+    (after the headline region, not part of it): median, 10th and 90th percentile in microseconds."""
+    import paper_2007_13055_amd as lib
+    fn = lambda: lib.bsr_spmm(W, X, Y)
+    us = sorted(_time_steps(fn, steps, 0, graph_chunk)[1] / steps * 1e6 for _ in range(repeats))
+    pick = lambda q: us[min(len(us) - 1, int(round(q * (len(us) - 1))))]
+    return {"repeats": repeats, "steps_each": steps, "median_us": pick(0.5), "p10_us": pick(0.1), "p90_us": pick(0.9)}
 
 
 def _launch_floor(steps, graph_chunk):
@@ -318,6 +328,7 @@ def main():
         "roofline": _roofline(p, r["event_s"] / a.steps),
         "eager_ms_per_step": r["eager_wall_s"] / a.steps * 1e3,
         "launch_floor_us": _launch_floor(a.steps, chunk) * 1e6,
+        "spread": _spread(p, W, r["X"], r["Y"], min(a.steps, 200), chunk if min(a.steps, 200) % max(chunk, 1) == 0 else 0),
     }
     out["cpu_baseline"] = None if a.no_cpu else _cpu_baseline(p)
 
