@@ -138,16 +138,6 @@ int oracle_bsr_spmm_rows(int64_t m, int64_t k, int64_t n, int32_t b_r, int32_t b
     return ORACLE_OK;
 }
 
-/* The whole product: Y, S are [m][n]. */
-int oracle_bsr_spmm(int64_t m, int64_t k, int64_t n, int32_t b_r, int32_t b_c, int64_t nnzb,
-                    const float* X, const float* block_data,
-                    const int32_t* block_indices, const int32_t* index_pointer,
-                    double* Y, double* S)
-{
-    return oracle_bsr_spmm_rows(m, k, n, b_r, b_c, nnzb, X, block_data, block_indices,
-                                index_pointer, m, NULL, Y, S);
-}
-
 /*
  * The sibling product  Z = G * W  (G dense (m, n), same BSR arrays of W; Z is (m, k)).
  *

@@ -96,13 +96,22 @@ def test_config_full_size_wave_path(oracle_mod, cid):
     check(Yg, Yo, So, p.tau, f"config {cid} wave")
 
 
+def _config5_rows(m, seed):
+    """Rows of X the oracle computes for configuration 5: one seeded row out of every 32 consecutive rows (so
+    every wavefront's slice of every m-tile of every kernel that may take the product is compared, 256 rows),
+    plus tile edges and the first and last rows."""
+    rng = np.random.default_rng(seed)
+    per_slice = (np.arange(0, m, 32) + rng.integers(0, 32, size=(m + 31) // 32)).clip(max=m - 1)
+    edges = [0, 1, 31, 32, 63, 64, 127, 128, 255, 256, 4095, 4096, m - 2, m - 1]
+    return sorted(set(per_slice.tolist() + edges))
+
+
 def test_config5_full_size_sampled_rows(oracle_mod):
-    """8192 x 8192 x 8192 fp16: the GPU computes everything, the oracle the sampled rows
-    (tile edges, first / last rows, a seeded random set)."""
+    """8192 x 8192 x 8192 fp16: the GPU computes everything, the oracle the sampled rows (one in every
+    32-row slice, tile edges, first / last rows)."""
     p = wl.config(5)
-    rng = np.random.default_rng(5)
-    rows = sorted(set([0, 1, 31, 32, 63, 64, 127, 128, 255, 256, 4095, 4096, 8190, 8191]
-                      + rng.integers(0, p.m, size=50).tolist()))
+    rows = _config5_rows(p.m, 5)
+    assert all(any(32 * s <= r < 32 * s + 32 for r in rows) for s in range(p.m // 32))
     Yo, So = oracle_of(oracle_mod, p, rows=rows)
     Yg, W = gpu_product(p, rows=rows)
     check(Yg, Yo, So, p.tau, "config 5 sampled rows", out_dtype=p.out_dtype)
@@ -122,7 +131,7 @@ def _gradient_like(p, seed):
 def test_config_full_size_sampled_product(oracle_mod, cid):
     """D = (G^T X) at the stored blocks on the five configurations at full size, launched as bench.py
     launches it.  The GPU computes every block; the oracle every block (1-4) or, for configuration 5, a
-    sample of blocks: first, last, some of the longest block-row, a seeded random set."""
+    sample of blocks: first, last, some of the longest block-row, one of every block-row, a seeded random set."""
     import torch
     import paper_2007_13055_amd as lib
     p = wl.config(cid)
@@ -139,8 +148,11 @@ def test_config_full_size_sampled_product(oracle_mod, cid):
         counts = np.diff(p.index_pointer)
         longest = int(np.argmax(counts))
         a = int(p.index_pointer[longest])
+        rng = np.random.default_rng(5)
+        starts = p.index_pointer[:-1][counts > 0]
+        per_row = starts + (rng.random(starts.shape[0]) * counts[counts > 0]).astype(np.int64)   # one block of every block-row
         pick = np.unique(np.concatenate([[0, p.nnzb - 1], a + np.array([0, 1, 2, 63, 64, int(counts[longest]) - 1]),
-                                         np.random.default_rng(5).integers(0, p.nnzb, size=40)]))
+                                         per_row, rng.integers(0, p.nnzb, size=40)]))
         rows = np.repeat(np.arange(p.n // p.bs_r), counts)[pick]
         idx = p.block_indices[pick]
         ptr = np.concatenate([[0], np.cumsum(np.bincount(rows, minlength=p.n // p.bs_r))]).astype(np.int32)
@@ -155,7 +167,7 @@ def test_config_full_size_sampled_product(oracle_mod, cid):
 @pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
 def test_config_full_size_transposed_sibling(oracle_mod, cid):
     """Z = G * W through the handle of W^T on the five configurations at full size; configuration 5 against
-    the oracle on sampled rows of G (a row of Z depends on that row of G only)."""
+    the oracle on sampled rows of G, one in every 32-row slice (a row of Z depends on that row of G only)."""
     import torch
     import paper_2007_13055_amd as lib
     p = wl.config(cid)
@@ -163,8 +175,7 @@ def test_config_full_size_transposed_sibling(oracle_mod, cid):
     WT = lib.bsr_create_transposed(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype=p.in_dtype)
     Z = lib.bsr_spmm(WT, to_device(G, p.in_dtype), y_dtype=p.out_dtype)
     torch.cuda.synchronize()
-    rows = np.arange(p.m) if cid < 5 else np.unique(np.concatenate(
-        [[0, 1, 127, 128, 4095, 4096, p.m - 1], np.random.default_rng(6).integers(0, p.m, size=40)]))
+    rows = np.arange(p.m) if cid < 5 else np.array(_config5_rows(p.m, 6))
     Zo, So = oracle_mod.bsr_spmm_w(G[rows], p.block_data, p.block_indices, p.index_pointer, p.k)
     Zg = Z[torch.as_tensor(rows, device="cuda")].double().cpu().numpy()
     check(Zg, Zo, So, p.tau, f"config {cid} transposed sibling", out_dtype=p.out_dtype)
@@ -298,6 +309,49 @@ def test_degenerate_sizes_and_errors():
         buf = torch.zeros(4 * 15 + 1, device="cuda")
         lib.bsr_spmm(Wodd, buf[1:].view(4, 15))
     assert e.value.status == 6
+
+
+
+def test_products_on_other_streams_than_create(oracle_mod):
+    """The handle is created on one stream and used at once on two others with two different m (two work-item
+    tables of the k-split kernel in flight): the products wait on the device for the plan upload and for each
+    other's table upload."""
+    import torch
+    import paper_2007_13055_amd as lib
+    rng = np.random.default_rng(78)
+    R, C, bs = 40, 24, 32
+    counts = rng.integers(0, 21, size=R)
+    ps = [wl.make_problem("st", m, C * bs, R * bs, bs, bs, "f32", "f32", ("counts", counts), ("normal", 1.0),
+                          ("normal", 1.0), 601) for m in (330, 1000)]
+    sa, sb, sc = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    Xs = [to_device(p.X, "f32") for p in ps]
+    torch.cuda.synchronize()
+    with torch.cuda.stream(sa):
+        W = lib.bsr_create(ps[0].n, ps[0].k, ps[0].block_data, ps[0].block_indices, ps[0].index_pointer, dtype="f32")
+    Ys = []
+    for rep in range(2):                                  # second round: the tables are cached
+        for p, X, s in zip(ps, Xs, (sb, sc)):
+            with torch.cuda.stream(s):
+                Ys.append(lib.bsr_spmm(W, X))
+    torch.cuda.synchronize()
+    for i, Y in enumerate(Ys):
+        p = ps[i % 2]
+        Yo, So = oracle_of(oracle_mod, p)
+        check(Y.double().cpu().numpy(), Yo, So, p.tau, f"streams, m={p.m}, round {i // 2}")
+
+
+def test_no_reduction_dimension():
+    """k = 0 (hence nothing stored), n > 0, many rows, 16x16 bf16 blocks: every kernel family stores zeros."""
+    import torch
+    import paper_2007_13055_amd as lib
+    W = lib.bsr_create(64, 0, np.zeros((0, 16, 16), np.float32), [], [0, 0, 0, 0, 0], dtype="bf16")
+    for m in (300, 5):
+        X = torch.zeros((m, 0), dtype=torch.bfloat16, device="cuda")
+        for path in (0, WAVE, MFMA):
+            Y = torch.full((m, 64), float("nan"), dtype=torch.bfloat16, device="cuda")
+            lib.bsr_spmm_ex(W, X, Y, path=path)
+            torch.cuda.synchronize()
+            assert torch.all(Y == 0), (m, path)
 
 
 def test_sampled_product_degenerate_sizes_and_errors():
