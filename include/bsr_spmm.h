@@ -117,11 +117,17 @@ void bsr_destroy(bsr_matrix* W);
  *   y_dtype W's dtype or BSR_F32; the fp32 accumulator is rounded to nearest-even on store
  *   m       any value >= 0 (m == 0 returns BSR_OK without device work)
  * Every element of Y is written; columns of an empty block-row are exact zeros.  Asynchronous on
- * `hip_stream`; no hidden synchronisation (a call with a new m may wait for the host side of the
- * previous m's work-list upload).  Products with the same m may run concurrently on one
- * handle (unless they use lent scratch, see bsr_set_scratch); products with different m share a
- * per-m work list in the workspace, uploaded on the call's stream, so keep them ordered on one
- * stream.
+ * `hip_stream`; no hidden synchronisation.  A product may be queued on any stream: until the plan
+ * upload that bsr_create() queued on its own stream has finished, products make their stream wait
+ * for it (an event wait on the device, not on the host).  Products on one handle may run
+ * concurrently (unless they use lent scratch, see bsr_set_scratch): some kernels read a per-m work
+ * list that the first product of that m uploads into the workspace (the handle keeps the lists of
+ * the 4 most recent values of m; other streams wait for that upload the same way).  With more than
+ * 4 distinct m in flight at once on one handle a list may be replaced while an earlier product still
+ * reads it: keep such products ordered on one stream.
+ * NaN or Inf in X: kernels that fill their last, partial group of blocks with zero-valued dummy
+ * blocks multiply those zeros by real entries of X (the thin-block kernels: by column 0 of X), so a
+ * non-finite entry there can reach outputs it does not belong to.  Finite inputs are unaffected.
  * Errors: NULL, SHAPE (m < 0 or m*max(k,n) >= 2^31), DTYPE, ALIGN, HIP.
  */
 bsr_status bsr_spmm(const bsr_matrix* W, int64_t m, const void* X_dev, void* Y_dev,
@@ -225,7 +231,18 @@ bsr_status bsr_transpose_values(bsr_dtype dtype, int32_t bs_r, int32_t bs_c, int
 bsr_status bsr_sddmm(const bsr_matrix* W, int64_t m, const void* G_dev, const void* X_dev, void* D_dev,
                      bsr_dtype d_dtype, void* hip_stream);
 
-/* Static, human-readable text for a status code. */
+/*
+ * Measurement helper for the benchmark, not part of the product (no passage of the paper defines it): one
+ * launch of a kernel that only issues independent matrix-core instructions of the given input type
+ * (8 accumulator chains per wavefront, 32 wavefronts per CU, `iters` rounds, no memory traffic), so that
+ * roofline fractions can be quoted against the rate this chip delivers as well as the published peak.
+ *   sink_dev   DEVICE, 4 bytes, never written in practice     flops_out  HOST: the flops the launch performs
+ * Asynchronous on hip_stream; time it with events.  Errors: NULL, SHAPE (iters outside [1, 2^20]), DTYPE, HIP.
+ */
+bsr_status bsr_probe_mfma(bsr_dtype dtype, int32_t iters, void* sink_dev, void* hip_stream, double* flops_out);
+
+/* Static, human-readable text for a status code.  (Like bsr_workspace_size(), bsr_destroy(), bsr_query_path(),
+ * bsr_scratch_size() and bsr_set_scratch(), a housekeeping call that no passage of the paper defines.) */
 const char* bsr_status_string(bsr_status s);
 
 #ifdef __cplusplus

@@ -55,10 +55,13 @@ def load_library():
     lib.bsr_transpose_pattern.argtypes = [i64, i64, i32, i32, i64, vp, vp, vp, vp, vp]
     lib.bsr_transpose_values.argtypes = [ctypes.c_int, i32, i32, i64, vp, vp, vp, vp]
     lib.bsr_sddmm.argtypes = [vp, i64, vp, vp, vp, ctypes.c_int, vp]
+    lib.bsr_probe_mfma.argtypes = [ctypes.c_int, i32, vp, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.bsr_probe_mfma.restype = ctypes.c_int
     lib.bsr_status_string.argtypes = [ctypes.c_int]
     lib.bsr_status_string.restype = ctypes.c_char_p
-    for f in ("bsr_validate", "bsr_workspace_size", "bsr_create", "bsr_spmm", "bsr_spmm_ex", "bsr_query_path",
-              "bsr_scratch_size", "bsr_set_scratch"):
+    for f in ("bsr_validate", "bsr_workspace_size", "bsr_create", "bsr_spmm", "bsr_spmm_ex",
+              "bsr_query_path", "bsr_scratch_size", "bsr_set_scratch", "bsr_tune", "bsr_tune_result",
+              "bsr_transpose_pattern", "bsr_transpose_values", "bsr_sddmm"):
         getattr(lib, f).restype = ctypes.c_int
     _lib = lib
     return lib

@@ -30,7 +30,7 @@ size_t item_table_bytes(int64_t R)
     // the table never holds more than 2*kMaxKsplitItems + 256 descriptors, and a W with R block-rows
     // has at most kMaxKsplitItems items when the kernel is used at all
     const size_t items = (size_t)std::min<int64_t>(std::max<int64_t>(R, 1) * 256, 2 * kMaxKsplitItems + 256);
-    return items * kRowDescWords * sizeof(int32_t);
+    return items * kRowDescWords * sizeof(int32_t);   // one table; the workspace holds kItemSlots of them
 }
 
 size_t plan_bytes(int64_t R, int64_t nnzb)
@@ -42,7 +42,7 @@ size_t plan_bytes(int64_t R, int64_t nnzb)
     // (at most one per stored block)
     const size_t per_row = 4 + 8 * (size_t)kRowDescWords + 4 + 16 * (size_t)kStripeChunkPairs + 16;
     // + 32 bytes per stored block for the sampled product: its block-row (4), runs (8), tiles (16 + 4)
-    size_t b = per_row * (size_t)R + 52 * (size_t)nnzb + 4096 + item_table_bytes(R);
+    size_t b = per_row * (size_t)R + 52 * (size_t)nnzb + 4096 + kItemSlots * item_table_bytes(R);
     return (b + 255) & ~(size_t)255;
 }
 
@@ -85,14 +85,33 @@ tune_opts read_tune_env()
 // first on the least loaded CU -- all m-tiles of a block-row on one XCD, so the block-row's W
 // blocks are fetched into one L2 only -- and writes the table level by level: entry c + #CUs*level
 // is the level-th item of CU c, or an empty descriptor (block-row -1) that makes the workgroup exit.
-int ksplit_items(const bsr_matrix* W, int tiles, hipStream_t stream)
+void order_after_upload(hipStream_t stream, hipEvent_t ev, std::atomic<bool>& landed)
+{
+    if (!ev || landed.load(std::memory_order_acquire)) return;
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cs) != hipSuccess) { (void)hipGetLastError(); return; }
+    if (cs != hipStreamCaptureStatusNone) return;
+    if (hipEventQuery(ev) == hipSuccess) { landed.store(true, std::memory_order_release); return; }
+    (void)hipGetLastError();                          // hipErrorNotReady is not an error of the product
+    (void)hipStreamWaitEvent(stream, ev, 0);
+    (void)hipGetLastError();
+}
+
+int ksplit_items(const bsr_matrix* W, int tiles, hipStream_t stream, const int32_t** table_out)
 {
     std::lock_guard<std::mutex> lock(W->item_mu);
-    if (W->item_tiles == tiles) return W->item_grid;
-    int n_cu = 0;
-    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, 0) != hipSuccess || n_cu <= 0) n_cu = 256;
+    bsr_matrix::item_table* slot = nullptr;
+    for (auto& t : W->item_tables)
+        if (t.tiles == tiles) slot = &t;
+    if (slot) {
+        slot->last_use = ++W->item_clock;
+        *table_out = W->item_desc + (size_t)(slot - W->item_tables) * W->item_capacity * kRowDescWords;
+        order_after_upload(stream, slot->uploaded, slot->landed);
+        return slot->grid;
+    }
+    const int n_cu = W->n_cu;
     constexpr int kXcds = 8;
-    if (n_cu % kXcds != 0) return 0;
+    if (n_cu <= 0 || n_cu % kXcds != 0) return 0;
     const int R = W->R;
     std::vector<int64_t> cu_load((size_t)n_cu, 0), xcd_load(kXcds, 0);
     std::vector<std::vector<int64_t>> lists((size_t)n_cu);       // (slot << 20 | tile) per CU, in placement order
@@ -112,14 +131,22 @@ int ksplit_items(const bsr_matrix* W, int tiles, hipStream_t stream)
     for (const auto& l : lists) levels = std::max(levels, l.size());
     const size_t grid = levels * (size_t)n_cu;
     if (grid == 0 || grid > W->item_capacity) return 0;
+    for (auto& t : W->item_tables)                    // an unused table, else the least recently used one
+        if (t.tiles < 0) { slot = &t; break; }
+    if (!slot) {
+        slot = &W->item_tables[0];
+        for (auto& t : W->item_tables)
+            if (t.last_use < slot->last_use) slot = &t;
+    }
     const int32_t* base = W->staging.data() + (W->row_desc - W->row_order);   // host copy of the row descriptors
-    // the previous table's upload may still be reading item_host: wait for it before rewriting the
+    // a replaced table's upload may still be reading its host copy: wait for it before rewriting the
     // buffer (an event that was only captured into a graph cannot be waited for; its upload ran at
     // capture's warm-up or will read the buffer at replay, which a caller changing m must order itself)
-    if (W->item_uploaded) (void)hipEventSynchronize(W->item_uploaded);
-    W->item_host.assign(grid * kRowDescWords, 0);
+    if (slot->uploaded && !slot->landed.load(std::memory_order_acquire)) (void)hipEventSynchronize(slot->uploaded);
+    (void)hipGetLastError();
+    slot->host.assign(grid * kRowDescWords, 0);
     for (size_t b = 0; b < grid; ++b) {
-        int32_t* d = W->item_host.data() + b * kRowDescWords;
+        int32_t* d = slot->host.data() + b * kRowDescWords;
         const auto& l = lists[b % (size_t)n_cu];
         const size_t level = b / (size_t)n_cu;
         if (level >= l.size()) { d[0] = -1; continue; }
@@ -127,17 +154,20 @@ int ksplit_items(const bsr_matrix* W, int tiles, hipStream_t stream)
         std::memcpy(d, base + (size_t)s * kRowDescWords, sizeof(int32_t) * kRowDescWords);
         d[3] = t;
     }
-    if (hipMemcpyAsync(W->item_desc, W->item_host.data(), W->item_host.size() * sizeof(int32_t),
-                       hipMemcpyHostToDevice, stream) != hipSuccess)
+    int32_t* dev = W->item_desc + (size_t)(slot - W->item_tables) * W->item_capacity * kRowDescWords;
+    slot->tiles = -1;
+    if (hipMemcpyAsync(dev, slot->host.data(), slot->host.size() * sizeof(int32_t), hipMemcpyHostToDevice, stream) != hipSuccess)
         return 0;
-    if (!W->item_uploaded && hipEventCreateWithFlags(&W->item_uploaded, hipEventDisableTiming) != hipSuccess)
-        W->item_uploaded = nullptr;
-    if (W->item_uploaded) (void)hipEventRecord(W->item_uploaded, stream);
+    slot->landed.store(false, std::memory_order_release);
+    if (!slot->uploaded && hipEventCreateWithFlags(&slot->uploaded, hipEventDisableTiming) != hipSuccess)
+        slot->uploaded = nullptr;
+    if (slot->uploaded) (void)hipEventRecord(slot->uploaded, stream);
     (void)hipGetLastError();                          // a refused record (stream capture) is not an error of the product
-    W->item_tiles = tiles;
-    W->item_grid = (int)grid;
-    W->item_cus = n_cu;
-    return W->item_grid;
+    slot->tiles = tiles;
+    slot->grid = (int)grid;
+    slot->last_use = ++W->item_clock;
+    *table_out = dev;
+    return slot->grid;
 }
 
 extern "C" {
@@ -195,6 +225,11 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
     W->R = (int32_t)R; W->C = (int32_t)(k / bs_c);
     W->dtype = dtype;
     W->data = block_data_dev; W->indices = block_indices_dev; W->indptr = index_pointer_dev;
+    W->env_tune = read_tune_env();                    // the development knob is read once per handle
+    if (hipGetDevice(&W->device) != hipSuccess) W->device = 0;
+    if (hipDeviceGetAttribute(&W->n_cu, hipDeviceAttributeMultiprocessorCount, W->device) != hipSuccess || W->n_cu <= 0)
+        W->n_cu = 256;
+    (void)hipGetLastError();
 
     // ---- plan: block-rows by stored-block count, longest first (stable, so equal rows keep
     //      their natural order and neighbouring rows stay neighbours in the launch) ----
@@ -415,7 +450,7 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
         W->item_capacity = item_table_bytes(R) / (kRowDescWords * sizeof(int32_t));
     }
     // the plan must fit what bsr_workspace_size promised (its bound is per block-row and per stored block)
-    if (sizeof(int32_t) * words + item_table_bytes(R) > workspace_bytes) { delete W; return BSR_ERR_WORKSPACE; }
+    if (sizeof(int32_t) * words + kItemSlots * item_table_bytes(R) > workspace_bytes) { delete W; return BSR_ERR_WORKSPACE; }
     if (R > 0) {
         hipError_t e = hipMemcpyAsync(workspace_dev, W->staging.data(), sizeof(int32_t) * words,
                                       hipMemcpyHostToDevice, (hipStream_t)hip_stream);
@@ -433,7 +468,9 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
 void bsr_destroy(bsr_matrix* W)
 {
     if (!W) return;
-    for (hipEvent_t e : {W->plan_uploaded, W->item_uploaded}) {   // uploads read the handle's host buffers
+    std::vector<hipEvent_t> events{W->plan_uploaded};
+    for (const auto& t : W->item_tables) events.push_back(t.uploaded);
+    for (hipEvent_t e : events) {                     // uploads read the handle's host buffers
         if (!e) continue;
         (void)hipEventSynchronize(e);
         (void)hipEventDestroy(e);
@@ -491,6 +528,10 @@ bsr_status check_product_args(const bsr_matrix* W, int64_t m, const void* X_dev,
 // One product on a fixed family (never AUTO) with fixed settings.
 bsr_status run_product(const spmm_args& a, bsr_path path, const tune_opts& t)
 {
+    order_after_upload(a.stream, a.W->plan_uploaded, a.W->plan_landed);
+    // no stored block (k == 0 included): every kernel family would only store zeros; the wavefront
+    // kernels do that for any shape without touching X or W
+    if (a.W->nnzb == 0) return launch_wave(a, t);
     if (path == BSR_PATH_MFMA) {
         if (mfma_thin_supports(a.W)) return launch_mfma_thin(a, t);
         if (mfma_small_supports(a.W)) return launch_mfma_small(a, t);
@@ -508,7 +549,7 @@ bsr_status bsr_spmm_ex(const bsr_matrix* W, int64_t m, const void* X_dev, void* 
     if (path != BSR_PATH_AUTO && path != BSR_PATH_WAVE && path != BSR_PATH_MFMA) return BSR_ERR_UNSUPPORTED;
     const bsr_status st = check_product_args(W, m, X_dev, Y_dev, y_dtype);
     if (st != BSR_OK || m == 0 || W->n == 0) return st;
-    tune_opts t = read_tune_env();
+    tune_opts t = W->env_tune;
     if (path == BSR_PATH_AUTO) {
         bool tuned = false;
         if (!t.from_env) {                            // what bsr_tune() remembered for this m, if anything

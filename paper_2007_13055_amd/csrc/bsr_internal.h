@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstddef>
 #include <cstdint>
 #include <map>
@@ -17,6 +18,7 @@ constexpr int kRowDescColsAt = 4;                 // word index of the first inl
 constexpr int kRowDescCols = kRowDescWords - kRowDescColsAt;
 constexpr int kMaxKsplitItems = 4096;             // the k-split kernel is used below this many (block-row, m-tile) items
 constexpr int kStripeChunkPairs = 6;              // the stripe kernel's pair table lists block-rows in chunks of this many pairs
+constexpr int kItemSlots = 4;                     // k-split work-item tables a handle keeps (one per recent m)
 
 // Development knobs, read from the environment variable BSR_SPMM_TUNE ("key=value,key=value"), and
 // the settings bsr_tune() remembers per m.  Unset keys are 0 and mean "the library's own choice".
@@ -59,15 +61,24 @@ struct bsr_matrix {
     // Pair table of the stripe kernel (16x16 blocks): pair_ptr[R+1], pairs[entries][4] (see bsr_create).
     const int32_t* pair_ptr = nullptr;
     const int32_t* pairs = nullptr;
-    int32_t* item_desc = nullptr;
-    size_t item_capacity = 0;                // descriptors that fit
+    int32_t* item_desc = nullptr;            // kItemSlots tables of item_capacity descriptors each
+    size_t item_capacity = 0;                // descriptors that fit one table
     std::vector<int32_t> slot_blocks;        // stored blocks per slot (host)
-    mutable std::mutex item_mu;              // guards the cache below
-    mutable int item_tiles = -1;             // m-tiles the cached table was built for (-1: none)
-    mutable int item_grid = 0;               // workgroups of the cached table
-    mutable int item_cus = 0;                // CUs the cached table was laid out for (entry b runs on CU b mod item_cus)
-    mutable std::vector<int32_t> item_host;  // host copy (kept alive for the asynchronous upload)
-    mutable hipEvent_t item_uploaded = nullptr;   // recorded behind the upload: waited for before item_host changes
+    // One cached table per recent number of m-tiles; the least recently used one is replaced.
+    struct item_table {
+        int tiles = -1;                      // m-tiles the table was built for (-1: none)
+        int grid = 0;                        // its workgroups
+        uint64_t last_use = 0;
+        std::vector<int32_t> host;           // host copy (kept alive for the asynchronous upload)
+        hipEvent_t uploaded = nullptr;       // recorded behind the upload
+        std::atomic<bool> landed{false};     // the upload is known to have finished
+    };
+    mutable std::mutex item_mu;              // guards the tables below
+    mutable item_table item_tables[kItemSlots];
+    mutable uint64_t item_clock = 0;
+    int n_cu = 256;                          // CUs of the device the handle was created on (entry b of a table runs on CU b mod n_cu)
+    int device = 0;                          // that device
+    tune_opts env_tune;                      // BSR_SPMM_TUNE as it was when the handle was created
     // Blocks smaller than an MFMA tile (bs_r, bs_c in {8,16}, not both 16; n and k multiples of 16),
     // grouped into 16x16 tiles of W (see bsr_create): descriptors of the tile-rows, longest first,
     // [sb_rows][kRowDescWords] = {tile-row, first entry, entries, 0, first tile-columns}; per entry the
@@ -93,7 +104,8 @@ struct bsr_matrix {
     int32_t empty_rows = 0;                  // block-rows with no stored block
     double mean_row_blocks = 0.0;
     std::vector<int32_t> staging;            // host copy of what was uploaded (kept for the async copy)
-    hipEvent_t plan_uploaded = nullptr;      // recorded behind that copy: bsr_destroy waits for it
+    hipEvent_t plan_uploaded = nullptr;      // recorded behind that copy: products on other streams and bsr_destroy wait for it
+    mutable std::atomic<bool> plan_landed{false};   // that copy is known to have finished
     // Optional per-call scratch lent by the caller (bsr_set_scratch): device memory some kernels
     // need beyond X, W and Y (the thin-block path keeps a transposed copy of X there).
     void* scratch = nullptr;
@@ -135,9 +147,14 @@ bool mfma_supports(const bsr_matrix* W);
 // matrix-core kernel variants (bsr_mfma*.hip)
 bsr_status launch_mfma_direct(const spmm_args& a, const tune_opts& t);
 bsr_status launch_mfma_ksplit(const spmm_args& a, const tune_opts& t);
-// Builds (or reuses) the k-split work-item table for `tiles` m-tiles and queues its upload on `stream`;
-// returns the number of workgroups, 0 if the table does not fit the workspace.
-int ksplit_items(const bsr_matrix* W, int tiles, hipStream_t stream);
+// Builds (or reuses) the k-split work-item table for `tiles` m-tiles, queues its upload on `stream` (or
+// makes `stream` wait for an upload another stream still has in flight); returns the number of
+// workgroups and the table's device address, 0 if the table does not fit the workspace.
+int ksplit_items(const bsr_matrix* W, int tiles, hipStream_t stream, const int32_t** table_out);
+// Makes `stream` wait (on the device) for the upload recorded as `ev`, unless it is known to have
+// finished.  Under stream capture nothing is recorded: an event from outside the capture cannot be
+// waited for there, and a caller that captures a handle's first product orders it itself.
+void order_after_upload(hipStream_t stream, hipEvent_t ev, std::atomic<bool>& landed);
 bsr_status launch_mfma_tile(const spmm_args& a, const tune_opts& t);
 bsr_status launch_mfma_stripe(const spmm_args& a, const tune_opts& t);
 bool mfma_stripe_supports(const bsr_matrix* W, int tm);   // 16x16 blocks, 16-bit type, tm rows of X fit in LDS

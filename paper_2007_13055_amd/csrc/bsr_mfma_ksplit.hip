@@ -253,8 +253,9 @@ bsr_status launch_ksplit_tile(const spmm_args& a, const tune_opts& tune)
     const int32_t* table = W->row_desc;
     int items = 0;
     if (tune.b != 1 && blocks > 256 && blocks <= kMaxKsplitItems) {
-        const int grid = ksplit_items(W, (int)tiles, a.stream);
-        if (grid > 0) { table = W->item_desc; items = W->item_cus; blocks = grid; }
+        const int32_t* item_table = nullptr;
+        const int grid = ksplit_items(W, (int)tiles, a.stream, &item_table);
+        if (grid > 0) { table = item_table; items = W->n_cu; blocks = grid; }
     }
     const size_t lds = (size_t)nw * geo::REGION;
     static const hipError_t attr =

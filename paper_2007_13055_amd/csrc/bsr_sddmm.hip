@@ -791,6 +791,7 @@ extern "C" bsr_status bsr_sddmm(const bsr_matrix* W, int64_t m, const void* G_de
     if (m * std::max<int64_t>(W->k, W->n) >= ((int64_t)1 << 31)) return BSR_ERR_SHAPE;
     if (((uintptr_t)G_dev | (uintptr_t)X_dev | (uintptr_t)D_dev) & 15u) return BSR_ERR_ALIGN;
     hipStream_t stream = (hipStream_t)hip_stream;
+    order_after_upload(stream, W->plan_uploaded, W->plan_landed);
     // m == 0 needs no special case: the kernels then read nothing and store zeros (an empty sum)
     const int mi = (int)m;
     if (W->dtype == BSR_F32) return launch_sddmm_types<float, float>(W, mi, G_dev, X_dev, D_dev, stream);
