@@ -1,17 +1,22 @@
 #!/usr/bin/env python3
 """Benchmark of bsr_spmm on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-all-configs] [--no-cpu] [--paper-grid] [--cold] [--sibling] [--peaks]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-all-configs] [--no-cpu]
+                    [--no-cold] [--no-peaks] [--paper-grid] [--sibling]
 
-A step is one whole product Y = X * W^T (one bsr_spmm call) on the headline workload, the
-"Transformer FFN weight" configuration (fp32, m=128, k=n=3072, 32x32 blocks, density 0.10), with
-X, W and Y already resident in HBM.  Prints ONE JSON line: effective TFLOP/s
-(2*m*nnzb*bs_r*bs_c per call), the roofline object of the product kernel, the CPU oracle timed on
-this machine's host cores, and a per-configuration table for the other four workloads.
+A step is one whole product Y = X * W^T (one bsr_spmm call) on the headline workload -- by default the
+"large skewed" configuration (fp16, m = k = n = 8192, 64x64 blocks, density 0.05, power-law block-rows), the
+largest of the five -- with X, W and Y already resident in HBM.  The K steps are timed as replays of a HIP
+graph of the launches (the graph holds the largest divisor of K that is at most --graph-chunk launches), with
+HIP events on the launch stream; plain launches are timed beside it.  Prints ONE JSON line: effective TFLOP/s
+(2*m*nnzb*bs_r*bs_c per call), the roofline object of the product kernel, the CPU oracle timed on this machine's
+host cores, what this chip delivers on a copy and on bare MFMA loops, and the same measurements for the
+other four workloads under "per_config".
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -33,6 +38,14 @@ WORKLOAD_TEXT = {
     "skewed": "skewed: X fp16 (8192,8192) N(0,1); W (8192,8192) BSR 64x64, 819 blocks (density 0.05), blocks per "
               "block-row by rank power law s=1.2; N(0,0.02); Y fp16",
 }
+CONFIG_ID = {"tiny": 1, "ffn": 2, "batched": 3, "thin": 4, "skewed": 5}
+
+
+def _graph_chunk(steps, limit):
+    """Launches per captured graph: the largest divisor of `steps` that is at most `limit` (0 = no graph)."""
+    if limit <= 0 or steps <= 0:
+        return 0
+    return max(d for d in range(1, min(steps, limit) + 1) if steps % d == 0)
 
 
 def _upload(p):
@@ -58,7 +71,7 @@ def _time_steps(fn, steps, warmup, graph_chunk):
         fn()
     torch.cuda.synchronize()
     run, mode = None, "eager"
-    if graph_chunk > 0 and steps % graph_chunk == 0:
+    if graph_chunk > 0 and steps % graph_chunk == 0 and steps > 0:
         try:
             side = torch.cuda.Stream()
             side.wait_stream(stream)
@@ -97,8 +110,9 @@ def _time_steps(fn, steps, warmup, graph_chunk):
 
 
 def _measured_traffic(name):
-    """HBM bytes per product from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary (None if absent).
-    A stored measurement of an earlier profiling run of this same command, not something timed here."""
+    """HBM-side bytes per product from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary (None if absent):
+    a stored reading of separate profiler runs of this command (profiles/hbm_traffic_all_workloads.md says
+    which), since counters cannot be read from inside the timed run."""
     try:
         with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
             return json.load(f).get(name)
@@ -110,14 +124,15 @@ def _roofline(p, sec_per_launch):
     """Both ceilings for one launch; the binding one is the slower of the two at peak."""
     t_hbm = p.algorithmic_bytes() / (PEAK_HBM_GBS * 1e9)
     t_mfma = p.flops / (PEAK_MFMA_TFLOPS[p.in_dtype] * 1e12)
-    traffic = _measured_traffic(p.name)
+    both = {"hbm_frac": t_hbm / sec_per_launch, "mfma_frac": t_mfma / sec_per_launch,
+            "algorithmic_bytes": p.algorithmic_bytes(), "flops": p.flops, "traffic": _measured_traffic(p.name),
+            "traffic_source": "profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE of this command)"}
     if t_mfma >= t_hbm:
         ach = p.flops / sec_per_launch / 1e12
         return {"bound": "mfma", "achieved": ach, "peak": PEAK_MFMA_TFLOPS[p.in_dtype], "unit": "TFLOP/s",
-                "frac": ach / PEAK_MFMA_TFLOPS[p.in_dtype], "traffic": traffic}
+                "frac": ach / PEAK_MFMA_TFLOPS[p.in_dtype], **both}
     ach = p.algorithmic_bytes() / sec_per_launch / 1e9
-    return {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
-            "traffic": traffic}
+    return {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, **both}
 
 
 def _bench_config(cid, steps, warmup, graph_chunk):
@@ -127,8 +142,8 @@ def _bench_config(cid, steps, warmup, graph_chunk):
     W, X, Y = _upload(p)
     fn = lambda: lib.bsr_spmm(W, X, Y)
     wall, ev, mode = _time_steps(fn, steps, warmup, graph_chunk)
-    eager_wall, _, _ = _time_steps(fn, steps, 0, 0)
-    return p, W, {"wall_s": wall, "event_s": ev, "mode": mode, "eager_wall_s": eager_wall,
+    eager_wall, eager_ev, _ = _time_steps(fn, steps, 0, 0)
+    return p, W, {"wall_s": wall, "event_s": ev, "mode": mode, "eager_wall_s": eager_wall, "eager_event_s": eager_ev,
                   "path": {1: "wave", 2: "mfma"}[lib.bsr_query_path(W, p.m)], "X": X, "Y": Y}
 
 
@@ -212,14 +227,14 @@ def _sibling(p, steps, chunk):
 
 
 def _cold(p, steps):
-    """The headline product with operands that are NOT resident in the 256 MB last-level cache: the calls
-    rotate through enough distinct (X, Y) pairs (and copies of W's values) that 1 GiB of other data
-    passes between two uses of the same buffer.  Plain launches (a graph would pin one buffer set)."""
+    """The product with operands that are NOT resident in the 256 MB last-level cache: the calls rotate
+    through enough distinct (W, X, Y) sets that 1 GiB of other data passes between two uses of the same
+    buffer.  Plain launches (a graph would pin one buffer set), so for the microsecond-scale workloads the
+    host's launch rate is part of the figure; "hbm_GBs_algorithmic" is the algorithmic bytes over that time."""
     import torch
     import paper_2007_13055_amd as lib
-    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
     per_set = p.algorithmic_bytes()
-    sets = max(2, min(512, int((1 << 30) // max(per_set, 1)) + 1))
+    sets = max(2, min(256, int((1 << 30) // max(per_set, 1)) + 1))
     Ws, Xs, Ys = [], [], []
     for _ in range(sets):
         W, X, Y = _upload(p)
@@ -236,58 +251,86 @@ def _cold(p, steps):
 
 
 def _measured_peaks():
-    """What this machine delivers on plain library work, for context beside the published peaks the roofline
-    uses: a 1 GiB device-to-device copy (read + written bytes per second) and large dense GEMMs through
-    torch (rocBLAS / hipBLASLt).  Library figures, not limits."""
+    """What this chip delivers, for context beside the published peaks the roofline uses: a 1 GiB
+    device-to-device copy (bytes read + written per second) and a loop of independent MFMAs without memory
+    traffic per input type (bsr_probe_mfma)."""
     import torch
+    import paper_2007_13055_amd as lib
+    so = lib.load_library()
     out = {}
     src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
     dst = torch.empty_like(src)
     _, ev, _ = _time_steps(lambda: dst.copy_(src), 20, 3, 0)
     out["copy_1GiB_GBs"] = 2 * src.numel() * 4 / (ev / 20) / 1e9
     del src, dst
-    for name, dt, nn in (("gemm_f32_8192_TFLOPs", torch.float32, 8192), ("gemm_bf16_8192_TFLOPs", torch.bfloat16, 8192)):
-        a = torch.randn(nn, nn, device="cuda", dtype=dt)
-        b = torch.randn(nn, nn, device="cuda", dtype=dt)
-        c = torch.empty(nn, nn, device="cuda", dtype=dt)
-        _, ev, _ = _time_steps(lambda: torch.mm(a, b, out=c), 10, 3, 0)
-        out[name] = 2 * nn ** 3 / (ev / 10) / 1e12
-        del a, b, c
+    sink = torch.zeros(1, device="cuda")
+    for name, code in (("f32", 0), ("f16", 1), ("bf16", 2)):
+        flops = ctypes.c_double(0.0)
+
+        def fn():
+            st = so.bsr_probe_mfma(code, 2000, sink.data_ptr(), torch.cuda.current_stream().cuda_stream, ctypes.byref(flops))
+            if st != 0:
+                raise RuntimeError(f"bsr_probe_mfma: status {st}")
+        _, ev, _ = _time_steps(fn, 5, 2, 0)
+        out[f"mfma_{name}_TFLOPs"] = flops.value / (ev / 5) / 1e12
     return out
 
 
-def _cpu_baseline(p, repeats=5):
+def _cpu_baseline(p):
+    """The oracle as it stands, timed on this machine's host cores.  Small workloads: the whole product, best of 5.
+    The skewed workload: every 4th row of X (2048 of 8192 rows, the whole W), one run, scaled by rows."""
+    import numpy as np
     import oracle
-    best = float("inf")
-    for _ in range(repeats):
+    if p.name == "skewed":
+        rows = np.arange(0, p.m, 4)
         t0 = time.perf_counter()
-        oracle.bsr_spmm(p.X, p.block_data, p.block_indices, p.index_pointer, p.n)
-        best = min(best, time.perf_counter() - t0)
-    return {"value": p.flops / best / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"the whole '{p.name}' workload, best of {repeats} runs ({best * 1e3:.1f} ms each); "
-                      "plain double-precision loops, a correctness reference and not a tuned CPU SpMM"}
+        oracle.bsr_spmm(p.X, p.block_data, p.block_indices, p.index_pointer, p.n, rows=rows)
+        best = time.perf_counter() - t0
+        flops = p.flops * rows.shape[0] / p.m
+        sample = (f"rows 0, 4, 8, ... of X ({rows.shape[0]} of {p.m} rows) against the whole W of the 'skewed' workload, one run "
+                  f"({best:.2f} s); throughput = that sample's flops over its time")
+    else:
+        best = float("inf")
+        for _ in range(5):
+            t0 = time.perf_counter()
+            oracle.bsr_spmm(p.X, p.block_data, p.block_indices, p.index_pointer, p.n)
+            best = min(best, time.perf_counter() - t0)
+        flops = p.flops
+        sample = f"the whole '{p.name}' workload, best of 5 runs ({best * 1e3:.1f} ms each)"
+    return {"value": flops / best / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": sample + "; plain double-precision loops, a correctness reference and not a tuned CPU SpMM"}
+
+
+def _entry(p, W, r, steps, chunk, floor_us, cold):
+    """Everything measured for one workload: graph-replay and plain-launch time, roofline, spread, cold operands."""
+    s = r["event_s"] / steps
+    sp_steps = min(steps, 200)
+    e = {"us_per_call": s * 1e6, "tflops": p.flops / s / 1e12, "path": r["path"], "launch": r["mode"],
+         "eager_us_per_call": r["eager_wall_s"] / steps * 1e6, "launch_floor_us": floor_us,
+         "roofline": _roofline(p, s),
+         "spread": _spread(p, W, r["X"], r["Y"], sp_steps, _graph_chunk(sp_steps, chunk))}
+    if cold:
+        e["cold"] = _cold(p, min(steps, 200))
+    return e
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--graph-chunk", type=int, default=100,
-                    help="launches per captured HIP graph (0 = plain launches only)")
-    ap.add_argument("--no-all-configs", action="store_true", help="skip the per-configuration table")
+                    help="most launches per captured HIP graph (0 = plain launches only)")
+    ap.add_argument("--no-all-configs", action="store_true", help="skip the other four workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
-    ap.add_argument("--cold", action="store_true",
-                    help="also time the headline product on operands rotated out of the last-level cache")
+    ap.add_argument("--no-cold", action="store_true", help="skip the runs on operands rotated out of the last-level cache")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the copy and MFMA-loop measurements of this chip")
     ap.add_argument("--sibling", action="store_true",
-                    help="also time the sibling product Z = G * W (through the handle of W^T) on the headline workload")
-    ap.add_argument("--peaks", action="store_true",
-                    help="also time a 1 GiB copy and two large torch GEMMs on this box and add them as 'measured_peaks'")
+                    help="also time the sibling products (Z = G * W through the handle of W^T, and the sampled product)")
     ap.add_argument("--paper-grid", action="store_true",
                     help="also time the 36 cells of the paper's own shape grid (m = 1, 8) and add them as 'paper_grid'")
-    ap.add_argument("--workload", default="ffn", choices=["tiny", "ffn", "batched", "thin", "skewed"],
-                    help="workload of the headline line (default: the FFN configuration); the others are for "
-                         "profiling one kernel at a time")
+    ap.add_argument("--workload", default="skewed", choices=list(CONFIG_ID),
+                    help="workload of the headline line (default: the largest, 'skewed')")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run 20 device-to-device copies of this many MiB and exit: the reference a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE reading is scaled by")
@@ -295,13 +338,14 @@ def main():
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the product needs no exchange between GPUs: "
                  "block-rows of W and rows of X both split without one). Use --gpus 1.")
+    if a.steps < 1 or a.warmup < 0:
+        sys.exit("bench.py: --steps must be at least 1 and --warmup non-negative")
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     import paper_2007_13055_amd as lib
     lib.load_library()
     torch.cuda.set_device(0)
-    chunk = a.graph_chunk if (a.graph_chunk > 0 and a.steps % a.graph_chunk == 0) else 0
     if a.copy_calibration > 0:
         src = torch.ones(a.copy_calibration * (1 << 20) // 4, device="cuda")
         dst = torch.empty_like(src)
@@ -310,51 +354,56 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_MiB": a.copy_calibration, "copies": 20}))
         return
-    headline = {"tiny": 1, "ffn": 2, "batched": 3, "thin": 4, "skewed": 5}[a.workload]
-    if headline == 5:
-        a.steps = min(a.steps, 200)
-        chunk = chunk if a.steps % max(chunk, 1) == 0 else 0
+    headline = CONFIG_ID[a.workload]
+    chunk = _graph_chunk(a.steps, a.graph_chunk)
+    floor_us = _launch_floor(a.steps, chunk) * 1e6
+    cold = not a.no_cold
 
     p, W, r = _bench_config(headline, a.steps, a.warmup, chunk)
-    sec = r["wall_s"] / a.steps
+    e = _entry(p, W, r, a.steps, a.graph_chunk, floor_us, cold)
+    sec = r["event_s"] / a.steps                      # HIP events on the launch stream: the clock of every figure below
     out = {
         "metric": "effective TFLOP/s of bsr_spmm (2*m*nnzb*bs_r*bs_c per call)",
         "value": p.flops / sec / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if p.in_dtype == "f32" else p.in_dtype, "data": "synthetic",
+        "dtype": p.in_dtype, "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[p.name],
                    "m": p.m, "k": p.k, "n": p.n, "bs_r": p.bs_r, "bs_c": p.bs_c, "nnzb": p.nnzb,
                    "path": r["path"], "launch": r["mode"], "seed": p.seed},
-        "roofline": _roofline(p, r["event_s"] / a.steps),
+        "roofline": e["roofline"],
+        "wall_ms_per_step": r["wall_s"] / a.steps * 1e3,
         "eager_ms_per_step": r["eager_wall_s"] / a.steps * 1e3,
-        "launch_floor_us": _launch_floor(a.steps, chunk) * 1e6,
-        "spread": _spread(p, W, r["X"], r["Y"], min(a.steps, 200), chunk if min(a.steps, 200) % max(chunk, 1) == 0 else 0),
+        "launch_floor_us": floor_us,
+        "spread": e["spread"],
     }
+    if cold:
+        out["cold"] = e["cold"]
     out["cpu_baseline"] = None if a.no_cpu else _cpu_baseline(p)
+    if not a.no_peaks:
+        out["measured_peaks"] = mp = _measured_peaks()
+        rf = out["roofline"]
+        rf["frac_of_measured_peak"] = (rf["achieved"] / mp["copy_1GiB_GBs"] if rf["bound"] == "hbm"
+                                       else rf["achieved"] / mp[f"mfma_{p.in_dtype}_TFLOPs"])
+    del W
 
     if not a.no_all_configs:
         table = {}
         for cid in (c for c in (1, 2, 3, 4, 5) if c != headline):
-            steps = 200 if cid == 5 else a.steps
-            ch = chunk if steps % max(chunk, 1) == 0 else 0
+            steps = 200 if cid == 5 else 1000
+            ch = _graph_chunk(steps, a.graph_chunk)
             q, Wq, rq = _bench_config(cid, steps, 20, ch)
-            s = rq["event_s"] / steps
-            t_hbm = q.algorithmic_bytes() / (PEAK_HBM_GBS * 1e9)
-            t_mfma = q.flops / (PEAK_MFMA_TFLOPS[q.in_dtype] * 1e12)
-            table[q.name] = {"us_per_call": s * 1e6, "tflops": q.flops / s / 1e12, "hbm_frac": t_hbm / s,
-                             "mfma_frac": t_mfma / s, "bound": "mfma" if t_mfma >= t_hbm else "hbm",
-                             "path": rq["path"], "launch": rq["mode"],
-                             "eager_us_per_call": rq["eager_wall_s"] / steps * 1e6}
+            table[q.name] = _entry(q, Wq, rq, steps, a.graph_chunk, floor_us, cold)
+            if not a.no_peaks:
+                rf = table[q.name]["roofline"]
+                rf["frac_of_measured_peak"] = (rf["achieved"] / mp["copy_1GiB_GBs"] if rf["bound"] == "hbm"
+                                               else rf["achieved"] / mp[f"mfma_{q.in_dtype}_TFLOPs"])
             del Wq
         out["per_config"] = table
     if a.paper_grid:
-        out["paper_grid"] = _paper_grid(a.steps, chunk)
-    if a.cold:
-        out["cold"] = _cold(p, min(a.steps, 1000))
+        out["paper_grid"] = _paper_grid(1000, 100)
     if a.sibling:
-        out["sibling"] = _sibling(p, a.steps, chunk)
-    if a.peaks:
-        out["measured_peaks"] = _measured_peaks()
+        import workloads as wl
+        out["sibling"] = _sibling(wl.config(headline), a.steps, chunk)
     print(json.dumps(out))
 
 
