@@ -48,7 +48,9 @@ typedef enum {
     BSR_ERR_WORKSPACE = 7,   /* workspace smaller than bsr_workspace_size() reports, or the chosen kernel needs
                                 scratch (bsr_scratch_size) that has not been lent with bsr_set_scratch */
     BSR_ERR_HIP = 8,         /* a HIP runtime call failed (launch, copy) */
-    BSR_ERR_UNSUPPORTED = 9  /* the requested kernel path cannot handle this block shape */
+    BSR_ERR_UNSUPPORTED = 9, /* the requested kernel path cannot handle this block shape */
+    BSR_ERR_SCRATCH_LIMIT = 10 /* bsr_spmm_static(): the product needs more scratch than the library's built-in
+                                  BSR_STATIC_SCRATCH_BYTES */
 } bsr_status;
 
 /* Which kernel family bsr_spmm_ex() uses. */
@@ -230,6 +232,28 @@ bsr_status bsr_transpose_values(bsr_dtype dtype, int32_t bs_r, int32_t bs_c, int
  */
 bsr_status bsr_sddmm(const bsr_matrix* W, int64_t m, const void* G_dev, const void* X_dev, void* D_dev,
                      bsr_dtype d_dtype, void* hip_stream);
+
+/*
+ * bsr_spmm() for callers that can neither allocate nor lend device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  (No passage of the paper defines this call; it is
+ * the product of bsr_spmm_ex(..., BSR_PATH_MFMA, ...) for the one kernel family that needs per-call scratch.)
+ * For thin blocks (bs_r = 16, bs_c = 1, fp32, y_dtype BSR_F32) the matrix-core path keeps a transposed copy
+ * of X in scratch; here that scratch is an array of BSR_STATIC_SCRATCH_BYTES bytes inside the library's code
+ * object instead of memory lent with bsr_set_scratch().  Every GPU the library is loaded on holds its own
+ * copy of the array until the process ends; its address is looked up once per device (at bsr_create(), else
+ * at the first call).  The call itself allocates and frees nothing, on the device or through any library.
+ *   Arguments as bsr_spmm().  m >= 1 rows need bsr_scratch_size(W, m) bytes: beyond the built-in size the
+ *   call returns BSR_ERR_SCRATCH_LIMIT and does no device work (256 x 4096: 4 MiB + 256 bytes).
+ *   Any other block shape or output type: BSR_ERR_UNSUPPORTED (no other kernel needs per-call scratch; use
+ *   bsr_spmm()).
+ * All calls on one GPU share that GPU's array, whatever the handle or stream: calls that overlap in time on
+ * one GPU race; keep them ordered on one stream.  The array keeps the last call's contents; nothing in it
+ * has to start at zero (each call first overwrites every entry it later reads for rows below m).
+ * Errors: as bsr_spmm(), plus SCRATCH_LIMIT and UNSUPPORTED.
+ */
+#define BSR_STATIC_SCRATCH_BYTES (8u << 20)
+bsr_status bsr_spmm_static(const bsr_matrix* W, int64_t m, const void* X_dev, void* Y_dev,
+                           bsr_dtype y_dtype, void* hip_stream);
 
 /*
  * Measurement helper for the benchmark, not part of the product (no passage of the paper defines it): one

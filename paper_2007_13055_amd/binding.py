@@ -46,6 +46,7 @@ def load_library():
     lib.bsr_destroy.restype = None
     lib.bsr_spmm.argtypes = [vp, i64, vp, vp, ctypes.c_int, vp]
     lib.bsr_spmm_ex.argtypes = [vp, i64, vp, vp, ctypes.c_int, ctypes.c_int, vp]
+    lib.bsr_spmm_static.argtypes = [vp, i64, vp, vp, ctypes.c_int, vp]
     lib.bsr_query_path.argtypes = [vp, i64, ctypes.POINTER(ctypes.c_int)]
     lib.bsr_tune.argtypes = [vp, i64, vp, vp, ctypes.c_int, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_int),
                              ctypes.POINTER(ctypes.c_float)]
@@ -59,7 +60,7 @@ def load_library():
     lib.bsr_probe_mfma.restype = ctypes.c_int
     lib.bsr_status_string.argtypes = [ctypes.c_int]
     lib.bsr_status_string.restype = ctypes.c_char_p
-    for f in ("bsr_validate", "bsr_workspace_size", "bsr_create", "bsr_spmm", "bsr_spmm_ex",
+    for f in ("bsr_validate", "bsr_workspace_size", "bsr_create", "bsr_spmm", "bsr_spmm_ex", "bsr_spmm_static",
               "bsr_query_path", "bsr_scratch_size", "bsr_set_scratch", "bsr_tune", "bsr_tune_result",
               "bsr_transpose_pattern", "bsr_transpose_values", "bsr_sddmm"):
         getattr(lib, f).restype = ctypes.c_int
@@ -239,6 +240,25 @@ def bsr_spmm_ex(W: BsrMatrix, X, Y=None, y_dtype=None, path=PATH_AUTO):
 
 def bsr_spmm(W: BsrMatrix, X, Y=None, y_dtype=None):
     return bsr_spmm_ex(W, X, Y, y_dtype, PATH_AUTO)
+
+
+STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def bsr_spmm_static(W: BsrMatrix, X, Y):
+    """bsr_spmm for thin-block W on the library's built-in scratch array: nothing is allocated or lent, so Y
+    must be given.  X (m, k) fp32, Y (m, n) fp32, both contiguous device tensors.  Returns Y."""
+    import torch
+    if X.dim() != 2 or X.shape[1] != W.k or _dtype_name(X) != W.dtype or not X.is_contiguous():
+        raise ValueError("X must be a contiguous (m, k) tensor of W's dtype")
+    m = int(X.shape[0])
+    if tuple(Y.shape) != (m, W.n) or _dtype_name(Y) != "f32" or not Y.is_contiguous():
+        raise ValueError("Y must be a contiguous (m, n) fp32 tensor")
+    st = load_library().bsr_spmm_static(W.handle, m, X.data_ptr(), Y.data_ptr(), BSR_F32,
+                                        torch.cuda.current_stream().cuda_stream)
+    if st != 0:
+        raise BsrError(st, "bsr_spmm_static")
+    return Y
 
 
 def bsr_tune(W: BsrMatrix, X, Y=None, y_dtype=None, trials: int = 20):

@@ -461,6 +461,9 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
             W->plan_uploaded = nullptr;
         (void)hipGetLastError();
     }
+    // thin blocks: look up the built-in scratch array's address for this device now, so that
+    // bsr_spmm_static() has no set-up left to do
+    if (mfma_thin_supports(W)) (void)mfma_thin_static_scratch(nullptr);
     *out = W;
     return BSR_OK;
 }
@@ -671,6 +674,21 @@ bsr_status bsr_spmm(const bsr_matrix* W, int64_t m, const void* X_dev, void* Y_d
     return bsr_spmm_ex(W, m, X_dev, Y_dev, y_dtype, BSR_PATH_AUTO, hip_stream);
 }
 
+bsr_status bsr_spmm_static(const bsr_matrix* W, int64_t m, const void* X_dev, void* Y_dev,
+                           bsr_dtype y_dtype, void* hip_stream)
+{
+    const bsr_status st = check_product_args(W, m, X_dev, Y_dev, y_dtype);
+    if (st != BSR_OK) return st;
+    if (!mfma_thin_supports(W) || y_dtype != BSR_F32) return BSR_ERR_UNSUPPORTED;
+    if (m == 0 || W->n == 0) return BSR_OK;
+    const spmm_args a{W, m, X_dev, Y_dev, y_dtype, (hipStream_t)hip_stream};
+    if (mfma_thin_scratch_bytes(W, m) > (size_t)BSR_STATIC_SCRATCH_BYTES) return BSR_ERR_SCRATCH_LIMIT;
+    order_after_upload(a.stream, W->plan_uploaded, W->plan_landed);
+    tune_opts t = W->env_tune;
+    if (W->nnzb == 0) return launch_wave(a, t);
+    return launch_mfma_thin_static(a, t);
+}
+
 const char* bsr_status_string(bsr_status s)
 {
     switch (s) {
@@ -684,6 +702,7 @@ const char* bsr_status_string(bsr_status s)
         case BSR_ERR_WORKSPACE: return "workspace smaller than bsr_workspace_size() reports";
         case BSR_ERR_HIP: return "HIP runtime call failed";
         case BSR_ERR_UNSUPPORTED: return "requested kernel path does not support this block shape";
+        case BSR_ERR_SCRATCH_LIMIT: return "the product needs more scratch than the library's built-in array (BSR_STATIC_SCRATCH_BYTES)";
     }
     return "unknown status";
 }

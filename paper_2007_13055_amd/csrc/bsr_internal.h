@@ -159,6 +159,11 @@ bsr_status launch_mfma_tile(const spmm_args& a, const tune_opts& t);
 bsr_status launch_mfma_stripe(const spmm_args& a, const tune_opts& t);
 bool mfma_stripe_supports(const bsr_matrix* W, int tm);   // 16x16 blocks, 16-bit type, tm rows of X fit in LDS
 bsr_status launch_mfma_thin(const spmm_args& a, const tune_opts& t);    // bs_r = 16, bs_c = 1, fp32; needs scratch
+// The same product on the library's built-in scratch array (no lent scratch needed); BSR_ERR_SCRATCH_LIMIT
+// when the product needs more than BSR_STATIC_SCRATCH_BYTES.
+bsr_status launch_mfma_thin_static(const spmm_args& a, const tune_opts& t);
+// Resolves the built-in scratch array's device address for the current device (once per device).
+bsr_status mfma_thin_static_scratch(void** out);
 bool mfma_thin_supports(const bsr_matrix* W);
 bsr_status launch_mfma_small(const spmm_args& a, const tune_opts& t);   // bs_r, bs_c in {8,16}, not both 16
 bool mfma_small_supports(const bsr_matrix* W);

@@ -186,14 +186,15 @@ bsr_status launch_transpose_f32(const float* X, float* XT, int m, int k, hipStre
     return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
 }
 
-bsr_status launch_mfma_thin(const spmm_args& a, const tune_opts& tune)
+namespace {
+
+// Transpose into `scratch` (at least mfma_thin_scratch_bytes() bytes, checked by the callers), then the product.
+bsr_status launch_thin_with_scratch(const spmm_args& a, const tune_opts& tune, void* scratch)
 {
     const bsr_matrix* W = a.W;
-    if (!mfma_thin_supports(W) || a.y_dtype != BSR_F32) return BSR_ERR_UNSUPPORTED;
     const int m = (int)a.m, n = (int)W->n, k = (int)W->k, R = W->R;
-    if (!W->scratch || W->scratch_bytes < mfma_thin_scratch_bytes(W, a.m)) return BSR_ERR_WORKSPACE;
     if ((a.m + 3) * W->k >= ((int64_t)1 << 30)) return BSR_ERR_SHAPE;      // byte offsets into XT are 32-bit
-    float* XT = static_cast<float*>(W->scratch);
+    float* XT = static_cast<float*>(scratch);
     hipLaunchKernelGGL(transpose_f32, dim3((k + 63) / 64, (m + 31) / 32), dim3(256), 0, a.stream,
                        (const float*)a.X, XT, m, k, (m + 3) & ~3);
     if (hipGetLastError() != hipSuccess) return BSR_ERR_HIP;
@@ -220,4 +221,60 @@ bsr_status launch_mfma_thin(const spmm_args& a, const tune_opts& tune)
     if (u <= 14) return go(std::integral_constant<int, 14>{});
     if (u <= 16) return go(std::integral_constant<int, 16>{});
     return go(std::integral_constant<int, 8>{});      // very long block-rows: several chunks of 32 blocks
+}
+
+}  // namespace
+
+bsr_status launch_mfma_thin(const spmm_args& a, const tune_opts& tune)
+{
+    const bsr_matrix* W = a.W;
+    if (!mfma_thin_supports(W) || a.y_dtype != BSR_F32) return BSR_ERR_UNSUPPORTED;
+    if (!W->scratch || W->scratch_bytes < mfma_thin_scratch_bytes(W, a.m)) return BSR_ERR_WORKSPACE;
+    return launch_thin_with_scratch(a, tune, W->scratch);
+}
+
+// ---- the library's own scratch, for callers that cannot allocate any (bsr_spmm_static) ----
+//
+// `scratch` is a device array that lives in this library's code object: every GPU the library is
+// loaded on holds its own copy, at its own address, until the process ends.  In host code the
+// name is only a handle for hipGetSymbolAddress(); the address it returns for the current device
+// is what the kernels get.
+namespace {
+
+static __device__ __align__(256) unsigned char scratch[BSR_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex static_scratch_mu;
+void* static_scratch_ptr[kMaxDevices] = {};          // per device, resolved once
+
+}  // namespace
+
+bsr_status mfma_thin_static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return BSR_ERR_HIP;
+    std::lock_guard<std::mutex> lock(static_scratch_mu);
+    if (!static_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return BSR_ERR_HIP;
+        }
+        static_scratch_ptr[dev] = ptr;
+    }
+    if (out) *out = static_scratch_ptr[dev];
+    return BSR_OK;
+}
+
+bsr_status launch_mfma_thin_static(const spmm_args& a, const tune_opts& tune)
+{
+    const bsr_matrix* W = a.W;
+    if (!mfma_thin_supports(W) || a.y_dtype != BSR_F32) return BSR_ERR_UNSUPPORTED;
+    if (mfma_thin_scratch_bytes(W, a.m) > (size_t)BSR_STATIC_SCRATCH_BYTES) return BSR_ERR_SCRATCH_LIMIT;
+    void* ptr = nullptr;
+    const bsr_status st = mfma_thin_static_scratch(&ptr);
+    if (st != BSR_OK) return st;
+    // nothing in the array has to start at zero: the transpose writes every entry of XT the product
+    // reads for rows below m, and what the last tile's gathers read beyond them is never stored
+    return launch_thin_with_scratch(a, tune, ptr);
 }

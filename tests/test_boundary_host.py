@@ -54,8 +54,8 @@ def test_workspace_size(lib):
 
 
 def test_status_strings(lib):
-    seen = {lib.bsr_status_string(s) for s in range(10)}
-    assert len(seen) == 10 and lib.bsr_status_string(0) == "ok"
+    seen = {lib.bsr_status_string(s) for s in range(11)}
+    assert len(seen) == 11 and lib.bsr_status_string(0) == "ok"
 
 
 def test_spmm_rejects_null_handle(lib):
