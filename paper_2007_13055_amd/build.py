@@ -23,7 +23,7 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-
 # Kernels in these files issue loads from inline assembly and place the waits themselves; the compiler
 # does not know such a register is still being filled, so a spill of one would store garbage.  The
 # build therefore fails if any kernel of these files spills a vector register.
-NO_SPILL = ("bsr_mfma_ksplit.hip", "bsr_mfma_tile.hip", "bsr_mfma_small.hip")
+NO_SPILL = ("bsr_mfma_ksplit.hip", "bsr_mfma_tile.hip", "bsr_mfma_small.hip", "bsr_mfma_group.hip")
 
 
 def _spilling_kernels(remarks: str):

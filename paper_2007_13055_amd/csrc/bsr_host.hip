@@ -33,7 +33,7 @@ size_t item_table_bytes(int64_t R)
     return items * kRowDescWords * sizeof(int32_t);   // one table; the workspace holds kItemSlots of them
 }
 
-size_t plan_bytes(int64_t R, int64_t nnzb)
+size_t plan_bytes(int64_t R, int64_t nnzb, int32_t bs_r, int32_t bs_c)
 {
     // row order (4R bytes) + row descriptors + pair pointers (4R) + pair entries (16 bytes each, at
     // most nnzb/2 + kStripeChunkPairs per block-row), each part padded to 256 bytes, + the k-split
@@ -43,6 +43,8 @@ size_t plan_bytes(int64_t R, int64_t nnzb)
     const size_t per_row = 4 + 8 * (size_t)kRowDescWords + 4 + 16 * (size_t)kStripeChunkPairs + 16;
     // + 32 bytes per stored block for the sampled product: its block-row (4), runs (8), tiles (16 + 4)
     size_t b = per_row * (size_t)R + 52 * (size_t)nnzb + 4096 + kItemSlots * item_table_bytes(R);
+    // row-group kernel (64x64 blocks): its step and tile lists and its per-m workgroup tables
+    b += sizeof(int32_t) * (group_plan_words(R, bs_r, bs_c, nnzb) + kItemSlots * group_table_words(R, bs_r, bs_c));
     return (b + 255) & ~(size_t)255;
 }
 
@@ -97,65 +99,35 @@ void order_after_upload(hipStream_t stream, hipEvent_t ev, std::atomic<bool>& la
     (void)hipGetLastError();
 }
 
-int ksplit_items(const bsr_matrix* W, int tiles, hipStream_t stream, const int32_t** table_out)
+int cached_table(const bsr_matrix* W, bsr_matrix::item_table* tables, int key, hipStream_t stream, int32_t* dev_base,
+                 size_t capacity_words, const std::function<int(std::vector<int32_t>&)>& build, const int32_t** table_out)
 {
     std::lock_guard<std::mutex> lock(W->item_mu);
     bsr_matrix::item_table* slot = nullptr;
-    for (auto& t : W->item_tables)
-        if (t.tiles == tiles) slot = &t;
+    for (int i = 0; i < kItemSlots; ++i)
+        if (tables[i].tiles == key) slot = &tables[i];
     if (slot) {
         slot->last_use = ++W->item_clock;
-        *table_out = W->item_desc + (size_t)(slot - W->item_tables) * W->item_capacity * kRowDescWords;
+        *table_out = dev_base + (size_t)(slot - tables) * capacity_words;
         order_after_upload(stream, slot->uploaded, slot->landed);
         return slot->grid;
     }
-    const int n_cu = W->n_cu;
-    constexpr int kXcds = 8;
-    if (n_cu <= 0 || n_cu % kXcds != 0) return 0;
-    const int R = W->R;
-    std::vector<int64_t> cu_load((size_t)n_cu, 0), xcd_load(kXcds, 0);
-    std::vector<std::vector<int64_t>> lists((size_t)n_cu);       // (slot << 20 | tile) per CU, in placement order
-    for (int s = 0; s < R; ++s) {
-        const int64_t w = std::max<int32_t>(W->slot_blocks[(size_t)s], 1);
-        const int x = (int)(std::min_element(xcd_load.begin(), xcd_load.end()) - xcd_load.begin());
-        for (int t = 0; t < tiles; ++t) {
-            int best = x;
-            for (int c = x; c < n_cu; c += kXcds)
-                if (cu_load[(size_t)c] < cu_load[(size_t)best]) best = c;
-            cu_load[(size_t)best] += w;
-            lists[(size_t)best].push_back(((int64_t)s << 20) | t);
-        }
-        xcd_load[(size_t)x] += w * tiles;
-    }
-    size_t levels = 0;
-    for (const auto& l : lists) levels = std::max(levels, l.size());
-    const size_t grid = levels * (size_t)n_cu;
-    if (grid == 0 || grid > W->item_capacity) return 0;
-    for (auto& t : W->item_tables)                    // an unused table, else the least recently used one
-        if (t.tiles < 0) { slot = &t; break; }
+    for (int i = 0; i < kItemSlots && !slot; ++i)      // an unused table, else the least recently used one
+        if (tables[i].tiles < 0) slot = &tables[i];
     if (!slot) {
-        slot = &W->item_tables[0];
-        for (auto& t : W->item_tables)
-            if (t.last_use < slot->last_use) slot = &t;
+        slot = &tables[0];
+        for (int i = 1; i < kItemSlots; ++i)
+            if (tables[i].last_use < slot->last_use) slot = &tables[i];
     }
-    const int32_t* base = W->staging.data() + (W->row_desc - W->row_order);   // host copy of the row descriptors
     // a replaced table's upload may still be reading its host copy: wait for it before rewriting the
     // buffer (an event that was only captured into a graph cannot be waited for; its upload ran at
     // capture's warm-up or will read the buffer at replay, which a caller changing m must order itself)
     if (slot->uploaded && !slot->landed.load(std::memory_order_acquire)) (void)hipEventSynchronize(slot->uploaded);
     (void)hipGetLastError();
-    slot->host.assign(grid * kRowDescWords, 0);
-    for (size_t b = 0; b < grid; ++b) {
-        int32_t* d = slot->host.data() + b * kRowDescWords;
-        const auto& l = lists[b % (size_t)n_cu];
-        const size_t level = b / (size_t)n_cu;
-        if (level >= l.size()) { d[0] = -1; continue; }
-        const int s = (int)(l[level] >> 20), t = (int)(l[level] & 0xFFFFF);
-        std::memcpy(d, base + (size_t)s * kRowDescWords, sizeof(int32_t) * kRowDescWords);
-        d[3] = t;
-    }
-    int32_t* dev = W->item_desc + (size_t)(slot - W->item_tables) * W->item_capacity * kRowDescWords;
     slot->tiles = -1;
+    const int grid = build(slot->host);
+    if (grid <= 0 || slot->host.size() > capacity_words) return 0;
+    int32_t* dev = dev_base + (size_t)(slot - tables) * capacity_words;
     if (hipMemcpyAsync(dev, slot->host.data(), slot->host.size() * sizeof(int32_t), hipMemcpyHostToDevice, stream) != hipSuccess)
         return 0;
     slot->landed.store(false, std::memory_order_release);
@@ -163,11 +135,52 @@ int ksplit_items(const bsr_matrix* W, int tiles, hipStream_t stream, const int32
         slot->uploaded = nullptr;
     if (slot->uploaded) (void)hipEventRecord(slot->uploaded, stream);
     (void)hipGetLastError();                          // a refused record (stream capture) is not an error of the product
-    slot->tiles = tiles;
-    slot->grid = (int)grid;
+    slot->tiles = key;
+    slot->grid = grid;
     slot->last_use = ++W->item_clock;
     *table_out = dev;
-    return slot->grid;
+    return grid;
+}
+
+int ksplit_items(const bsr_matrix* W, int tiles, hipStream_t stream, const int32_t** table_out)
+{
+    const int n_cu = W->n_cu;
+    constexpr int kXcds = 8;
+    if (n_cu <= 0 || n_cu % kXcds != 0) return 0;
+    auto build = [&](std::vector<int32_t>& host) -> int {
+        const int R = W->R;
+        std::vector<int64_t> cu_load((size_t)n_cu, 0), xcd_load(kXcds, 0);
+        std::vector<std::vector<int64_t>> lists((size_t)n_cu);       // (slot << 20 | tile) per CU, in placement order
+        for (int s = 0; s < R; ++s) {
+            const int64_t w = std::max<int32_t>(W->slot_blocks[(size_t)s], 1);
+            const int x = (int)(std::min_element(xcd_load.begin(), xcd_load.end()) - xcd_load.begin());
+            for (int t = 0; t < tiles; ++t) {
+                int best = x;
+                for (int c = x; c < n_cu; c += kXcds)
+                    if (cu_load[(size_t)c] < cu_load[(size_t)best]) best = c;
+                cu_load[(size_t)best] += w;
+                lists[(size_t)best].push_back(((int64_t)s << 20) | t);
+            }
+            xcd_load[(size_t)x] += w * tiles;
+        }
+        size_t levels = 0;
+        for (const auto& l : lists) levels = std::max(levels, l.size());
+        const size_t grid = levels * (size_t)n_cu;
+        if (grid == 0 || grid > W->item_capacity) return 0;
+        const int32_t* base = W->staging.data() + (W->row_desc - W->row_order);   // host copy of the row descriptors
+        host.assign(grid * kRowDescWords, 0);
+        for (size_t b = 0; b < grid; ++b) {
+            int32_t* d = host.data() + b * kRowDescWords;
+            const auto& l = lists[b % (size_t)n_cu];
+            const size_t level = b / (size_t)n_cu;
+            if (level >= l.size()) { d[0] = -1; continue; }
+            const int s = (int)(l[level] >> 20), t = (int)(l[level] & 0xFFFFF);
+            std::memcpy(d, base + (size_t)s * kRowDescWords, sizeof(int32_t) * kRowDescWords);
+            d[3] = t;
+        }
+        return (int)grid;
+    };
+    return cached_table(W, W->item_tables, tiles, stream, W->item_desc, W->item_capacity * kRowDescWords, build, table_out);
 }
 
 extern "C" {
@@ -196,7 +209,7 @@ bsr_status bsr_workspace_size(int64_t n, int64_t k, int32_t bs_r, int32_t bs_c, 
     *bytes = 0;
     bsr_status st = check_shape(n, k, bs_r, bs_c, nnzb);
     if (st != BSR_OK) return st;
-    *bytes = plan_bytes(n / bs_r, nnzb);
+    *bytes = plan_bytes(n / bs_r, nnzb, bs_r, bs_c);
     return BSR_OK;
 }
 
@@ -217,7 +230,7 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
         ((uintptr_t)block_indices_dev & 3u) || ((uintptr_t)index_pointer_dev & 3u))
         return BSR_ERR_ALIGN;
     const int64_t R = n / bs_r;
-    if (workspace_bytes < plan_bytes(R, nnzb)) return BSR_ERR_WORKSPACE;
+    if (workspace_bytes < plan_bytes(R, nnzb, bs_r, bs_c)) return BSR_ERR_WORKSPACE;
 
     bsr_matrix* W = new (std::nothrow) bsr_matrix();
     if (!W) return BSR_ERR_HIP;
@@ -445,12 +458,19 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
             words = (plist_at + plist.size() + 63) & ~(size_t)63;
         }
     }
-    {   // the work-item table sits behind everything else, 256-byte aligned
+    build_group_plan(W, index_pointer_host, block_indices_host, &words);
+    size_t upload_words = words;
+    {   // the per-m tables sit behind everything else, 256-byte aligned
         W->item_desc = const_cast<int32_t*>(W->row_order) + words;
         W->item_capacity = item_table_bytes(R) / (kRowDescWords * sizeof(int32_t));
+        words += kItemSlots * W->item_capacity * kRowDescWords;
+        W->grp_desc = const_cast<int32_t*>(W->row_order) + words;
+        W->grp_capacity = group_table_words(R, bs_r, bs_c) / 16;
+        words += kItemSlots * group_table_words(R, bs_r, bs_c);
     }
     // the plan must fit what bsr_workspace_size promised (its bound is per block-row and per stored block)
-    if (sizeof(int32_t) * words + kItemSlots * item_table_bytes(R) > workspace_bytes) { delete W; return BSR_ERR_WORKSPACE; }
+    if (sizeof(int32_t) * words > workspace_bytes) { delete W; return BSR_ERR_WORKSPACE; }
+    words = upload_words;
     if (R > 0) {
         hipError_t e = hipMemcpyAsync(workspace_dev, W->staging.data(), sizeof(int32_t) * words,
                                       hipMemcpyHostToDevice, (hipStream_t)hip_stream);

@@ -6,6 +6,7 @@
 #include <atomic>
 #include <cstddef>
 #include <cstdint>
+#include <functional>
 #include <map>
 #include <mutex>
 #include <vector>
@@ -76,6 +77,24 @@ struct bsr_matrix {
     mutable std::mutex item_mu;              // guards the tables below
     mutable item_table item_tables[kItemSlots];
     mutable uint64_t item_clock = 0;
+    // Row-group kernel (64x64 blocks of a 16-bit type, bsr_mfma_group.hip).  A group is up to 8 block-rows
+    // that one workgroup multiplies together, walking the union of their block-columns: per step one
+    // block-column (its X tile is staged once) and the stored blocks the group's rows have there.
+    //   grp_tiles    = per step the tiles to stage, in order: 0x80000000 | block-column, then for every row j of
+    //                  the group that stores a block there, in row order, its stored-block number | (j << 28)
+    //   grp_steps    = the steps of a group cut into batches of whole steps, at most 8 tiles each (a step
+    //                  of 9 tiles alone): tiles per batch
+    struct row_group {
+        int32_t row[8];                      // block-rows (-1: none)
+        int32_t steps_off, n_steps, tiles_off, n_tiles;
+        double cost;                         // estimated work per 64 rows of X
+    };
+    std::vector<row_group> groups;           // host
+    const int32_t* grp_steps = nullptr;      // device
+    const int32_t* grp_tiles = nullptr;      // device
+    int32_t* grp_desc = nullptr;             // device: kItemSlots workgroup tables of grp_capacity entries (16 words each)
+    size_t grp_capacity = 0;
+    mutable item_table grp_tables[kItemSlots];   // one per recent number of 64-row sub-tiles of X
     int n_cu = 256;                          // CUs of the device the handle was created on (entry b of a table runs on CU b mod n_cu)
     int device = 0;                          // that device
     tune_opts env_tune;                      // BSR_SPMM_TUNE as it was when the handle was created
@@ -151,11 +170,27 @@ bsr_status launch_mfma_ksplit(const spmm_args& a, const tune_opts& t);
 // makes `stream` wait for an upload another stream still has in flight); returns the number of
 // workgroups and the table's device address, 0 if the table does not fit the workspace.
 int ksplit_items(const bsr_matrix* W, int tiles, hipStream_t stream, const int32_t** table_out);
+// One cached per-m table out of `tables` (kItemSlots of them, `capacity_words` int32 each, starting at
+// `dev_base`): the one built for `key`, else `build` fills a host vector (returning the number of
+// workgroups, 0 = does not fit) that is uploaded into the least recently used slot on `stream`.
+// Returns the workgroups and the table's device address; 0 if there is no table.  Caller holds no lock.
+int cached_table(const bsr_matrix* W, bsr_matrix::item_table* tables, int key, hipStream_t stream, int32_t* dev_base,
+                 size_t capacity_words, const std::function<int(std::vector<int32_t>&)>& build, const int32_t** table_out);
 // Makes `stream` wait (on the device) for the upload recorded as `ev`, unless it is known to have
 // finished.  Under stream capture nothing is recorded: an event from outside the capture cannot be
 // waited for there, and a caller that captures a handle's first product orders it itself.
 void order_after_upload(hipStream_t stream, hipEvent_t ev, std::atomic<bool>& landed);
 bsr_status launch_mfma_tile(const spmm_args& a, const tune_opts& t);
+// Row-group kernel: 64x64 blocks of a 16-bit type whose plan bsr_create could build
+bsr_status launch_mfma_group(const spmm_args& a, const tune_opts& t);
+bool mfma_group_supports(const bsr_matrix* W);
+// Builds the row groups of W and appends their step and tile lists to the plan being staged (`words` = its
+// length so far, 64-word aligned on return); leaves W->groups empty when the shape is not the kernel's or a
+// list would not fit its LDS area.  group_plan_words / group_table_words: what the workspace must hold.
+void build_group_plan(bsr_matrix* W, const int32_t* index_pointer_host, const int32_t* block_indices_host, size_t* words);
+int build_group_table(const bsr_matrix* W, int n_sub, int cus_per_xcd, std::vector<int32_t>& host);
+size_t group_plan_words(int64_t R, int32_t bs_r, int32_t bs_c, int64_t nnzb);
+size_t group_table_words(int64_t R, int32_t bs_r, int32_t bs_c);
 bsr_status launch_mfma_stripe(const spmm_args& a, const tune_opts& t);
 bool mfma_stripe_supports(const bsr_matrix* W, int tm);   // 16x16 blocks, 16-bit type, tm rows of X fit in LDS
 bsr_status launch_mfma_thin(const spmm_args& a, const tune_opts& t);    // bs_r = 16, bs_c = 1, fp32; needs scratch

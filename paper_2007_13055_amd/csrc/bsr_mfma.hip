@@ -186,6 +186,7 @@ bsr_status launch_mfma(const spmm_args& a, const tune_opts& tune)
             if (t.a == 0) t.a = tall ? 1 : 2;
         }
     }
+    if (variant == 5) return launch_mfma_group(a, t);
     if (variant == 2) return launch_mfma_ksplit(a, t);
     if (variant == 3) return launch_mfma_tile(a, t);
     if (variant == 4) return launch_mfma_stripe(a, t);

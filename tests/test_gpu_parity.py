@@ -464,6 +464,61 @@ def test_stripe_kernel_variant(oracle_mod, monkeypatch, extra, dtype, out):
         assert np.array_equal(Yg, Yg2), "two runs differ: race"
 
 
+# ------------------------------------------------------------------ the row-group kernel (variant 5)
+@pytest.mark.parametrize("extra", ["", ",a=1", ",a=4", ",a=63"])
+@pytest.mark.parametrize("dtype,out", [("f16", "f16"), ("bf16", "bf16"), ("f16", "f32"), ("bf16", "f32")])
+def test_group_kernel_variant(oracle_mod, monkeypatch, extra, dtype, out):
+    """variant 5: 64x64 blocks of a 16-bit type, groups of up to 8 block-rows walking the union of their
+    block-columns.  Long, short, single-block and empty block-rows, more block-rows than one group holds, steps
+    with 1 to 8 blocks, ragged m; a = CUs per XCD the workgroup table assumes (how groups are split along m)."""
+    monkeypatch.setenv("BSR_SPMM_TUNE", "variant=5" + extra)
+    cases = [(5, np.array([3, 0, 9, 1])),
+             (64, np.array([12, 12, 11, 12, 10, 12, 12, 9, 1, 0, 2])),            # a heavy group with full steps
+             (130, np.array([0, 1, 2, 3, 20, 5, 0, 17, 9, 1, 1, 1, 1, 1, 1, 1, 1, 1, 4])),
+             (700, np.array([20, 18, 1, 0, 0, 7, 3, 3, 2, 1, 1, 15, 6]))]
+    for m, counts in cases:
+        C = 20
+        p = wl.make_problem("grp", m, C * 64, counts.shape[0] * 64, 64, 64, dtype, out, ("counts", counts),
+                            ("normal", 1.0), ("normal", 1.0), 1300 + m)
+        Yo, So = oracle_of(oracle_mod, p)
+        Yg, W = gpu_product(p, path=MFMA)
+        check(Yg, Yo, So, p.tau, f"group{extra} {dtype}->{out} m={m}", out_dtype=out)
+        Yg2, _ = gpu_product(p, path=MFMA, W=W)
+        assert np.array_equal(Yg, Yg2), "two runs differ: race"
+
+
+def test_group_kernel_small_integers_bitwise_duplicates_and_order(oracle_mod, monkeypatch):
+    """Exact data (any summation order gives the oracle's value bit for bit), with unsorted block-columns and a
+    block-column stored twice in one block-row (two steps of the same column)."""
+    monkeypatch.setenv("BSR_SPMM_TUNE", "variant=5")
+    p = wl.small_integer_problem(333, 12 * 64, 11 * 64, 64, 64, 0.5, seed=23, in_dtype="f16", out_dtype="f32", lo=-2, hi=2)
+    Yo, So = oracle_of(oracle_mod, p)
+    Yg, _ = gpu_product(p, path=MFMA)
+    assert np.array_equal(Yg, Yo)
+    rng = np.random.default_rng(24)
+    ptr = np.array([0, 4, 4, 7, 8], dtype=np.int32)
+    idx = np.array([2, 0, 2, 1, 3, 3, 0, 1], dtype=np.int32)                  # row 0: column 2 twice, unsorted; row 2: column 3 twice
+    data = rng.integers(-2, 3, size=(8, 64, 64)).astype(np.float32)
+    X = rng.integers(-2, 3, size=(70, 4 * 64)).astype(np.float32)
+    q = wl.Problem("dup", 70, 4 * 64, 4 * 64, 64, 64, "bf16", "f32", X, data, idx, ptr)
+    Yo, So = oracle_of(oracle_mod, q)
+    Yg, _ = gpu_product(q, path=MFMA)
+    assert np.array_equal(Yg, Yo)
+
+
+def test_group_kernel_config5_sampled_rows(oracle_mod, monkeypatch):
+    """The row-group kernel on the 8192^3 workload at full size, whatever the default choice is."""
+    monkeypatch.setenv("BSR_SPMM_TUNE", "variant=5")
+    p = wl.config(5)
+    rows = _config5_rows(p.m, 7)
+    Yo, So = oracle_of(oracle_mod, p, rows=rows)
+    Yg, W = gpu_product(p, rows=rows)
+    check(Yg, Yo, So, p.tau, "config 5, row-group kernel", out_dtype=p.out_dtype)
+    Yg32, _ = gpu_product(p, rows=rows, y_dtype="f32", W=W)
+    check(Yg32, Yo, So, p.tau, "config 5, row-group kernel, fp32 output")
+    assert np.array_equal(wl.round_to_storage(Yg32.astype(np.float32), "f16").astype(np.float64), Yg)
+
+
 @pytest.mark.parametrize("u", ["", "a=4", "a=8", "a=16", "a=6,b=1", "a=10,b=2", "b=4", "a=14,b=8"])
 def test_thin_mfma_path(oracle_mod, monkeypatch, u):
     """16x1 fp32 blocks on the matrix-core path: transposed copy of X in lent scratch, then gather + MFMA
