@@ -43,8 +43,8 @@ size_t plan_bytes(int64_t R, int64_t nnzb, int32_t bs_r, int32_t bs_c)
     const size_t per_row = 4 + 8 * (size_t)kRowDescWords + 4 + 16 * (size_t)kStripeChunkPairs + 16;
     // + 32 bytes per stored block for the sampled product: its block-row (4), runs (8), tiles (16 + 4)
     size_t b = per_row * (size_t)R + 52 * (size_t)nnzb + 4096 + kItemSlots * item_table_bytes(R);
-    // row-group kernel (64x64 blocks): its step and tile lists and its per-m workgroup tables
-    b += sizeof(int32_t) * (group_plan_words(R, bs_r, bs_c, nnzb) + kItemSlots * group_table_words(R, bs_r, bs_c));
+    // row-group kernel (64x64 blocks): its group descriptors and window records
+    b += sizeof(int32_t) * group_plan_words(R, bs_r, bs_c, nnzb);
     return (b + 255) & ~(size_t)255;
 }
 
@@ -464,9 +464,6 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
         W->item_desc = const_cast<int32_t*>(W->row_order) + words;
         W->item_capacity = item_table_bytes(R) / (kRowDescWords * sizeof(int32_t));
         words += kItemSlots * W->item_capacity * kRowDescWords;
-        W->grp_desc = const_cast<int32_t*>(W->row_order) + words;
-        W->grp_capacity = group_table_words(R, bs_r, bs_c) / 16;
-        words += kItemSlots * group_table_words(R, bs_r, bs_c);
     }
     // the plan must fit what bsr_workspace_size promised (its bound is per block-row and per stored block)
     if (sizeof(int32_t) * words > workspace_bytes) { delete W; return BSR_ERR_WORKSPACE; }

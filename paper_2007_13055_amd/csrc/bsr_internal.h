@@ -23,7 +23,7 @@ constexpr int kItemSlots = 4;                     // k-split work-item tables a 
 
 // Development knobs, read from the environment variable BSR_SPMM_TUNE ("key=value,key=value"), and
 // the settings bsr_tune() remembers per m.  Unset keys are 0 and mean "the library's own choice".
-//   variant  1 direct, 2 ksplit, 3 tile, 4 stripe  (matrix-core kernel variant)
+//   variant  1 direct, 2 ksplit, 3 tile, 4 stripe, 5 row groups + tile  (matrix-core kernel variant)
 //   nw       wavefronts per workgroup      mt   MFMA tiles along m per wavefront (wave path: rows of X
 //            per wavefront; ksplit: 1 = 16-row, 2 = 32-row tiles)
 //   a, b     per-variant: ksplit a = blocks per wavefront; tile a = blocks in flight, b-1 = long rows
@@ -77,24 +77,17 @@ struct bsr_matrix {
     mutable std::mutex item_mu;              // guards the tables below
     mutable item_table item_tables[kItemSlots];
     mutable uint64_t item_clock = 0;
-    // Row-group kernel (64x64 blocks of a 16-bit type, bsr_mfma_group.hip).  A group is up to 8 block-rows
-    // that one workgroup multiplies together, walking the union of their block-columns: per step one
-    // block-column (its X tile is staged once) and the stored blocks the group's rows have there.
-    //   grp_tiles    = per step the tiles to stage, in order: 0x80000000 | block-column, then for every row j of
-    //                  the group that stores a block there, in row order, its stored-block number | (j << 28)
-    //   grp_steps    = the steps of a group cut into batches of whole steps, at most 8 tiles each (a step
-    //                  of 9 tiles alone): tiles per batch
-    struct row_group {
-        int32_t row[8];                      // block-rows (-1: none)
-        int32_t steps_off, n_steps, tiles_off, n_tiles;
-        double cost;                         // estimated work per 64 rows of X
-    };
-    std::vector<row_group> groups;           // host
-    const int32_t* grp_steps = nullptr;      // device
-    const int32_t* grp_tiles = nullptr;      // device
-    int32_t* grp_desc = nullptr;             // device: kItemSlots workgroup tables of grp_capacity entries (16 words each)
-    size_t grp_capacity = 0;
-    mutable item_table grp_tables[kItemSlots];   // one per recent number of 64-row sub-tiles of X
+    // Row-group kernel (64x64 blocks of a 16-bit type, bsr_mfma_group.hip): the leading grp_slots slots (the
+    // longest block-rows) are multiplied in groups of up to 8 that share their X tiles; the tile kernel takes
+    // the slots behind them.  grp_desc = per group {8 block-rows (-1: none), first window record, windows, 0...}
+    // (16 words), grp_recs = the window records (16 words each, layout in bsr_mfma_group.hip).
+    int32_t grp_n = 0;                       // groups (0: the kernel is not used for this W)
+    int32_t grp_slots = 0;                   // leading slots they cover
+    int64_t grp_blocks = 0;                  // stored blocks of those slots
+    const int32_t* grp_desc = nullptr;       // device
+    const int32_t* grp_recs = nullptr;       // device
+    std::vector<int32_t> grp_host;           // host copy of both (descriptors first), for the plan checker
+    size_t grp_host_recs_at = 0;             // word offset of the records in grp_host
     int n_cu = 256;                          // CUs of the device the handle was created on (entry b of a table runs on CU b mod n_cu)
     int device = 0;                          // that device
     tune_opts env_tune;                      // BSR_SPMM_TUNE as it was when the handle was created
@@ -142,6 +135,7 @@ struct spmm_args {
     void* Y;
     bsr_dtype y_dtype;
     hipStream_t stream;
+    int first_slot = 0;                      // tile kernel: leave out the slots before this one (another kernel multiplies them)
 };
 
 tune_opts read_tune_env();
@@ -181,16 +175,15 @@ int cached_table(const bsr_matrix* W, bsr_matrix::item_table* tables, int key, h
 // waited for there, and a caller that captures a handle's first product orders it itself.
 void order_after_upload(hipStream_t stream, hipEvent_t ev, std::atomic<bool>& landed);
 bsr_status launch_mfma_tile(const spmm_args& a, const tune_opts& t);
-// Row-group kernel: 64x64 blocks of a 16-bit type whose plan bsr_create could build
+// Row-group kernel: the grouped (longest) block-rows of a W with 64x64 blocks of a 16-bit type; the caller
+// launches the tile kernel with first_slot = W->grp_slots for the rest
 bsr_status launch_mfma_group(const spmm_args& a, const tune_opts& t);
 bool mfma_group_supports(const bsr_matrix* W);
-// Builds the row groups of W and appends their step and tile lists to the plan being staged (`words` = its
-// length so far, 64-word aligned on return); leaves W->groups empty when the shape is not the kernel's or a
-// list would not fit its LDS area.  group_plan_words / group_table_words: what the workspace must hold.
+// Chooses the grouped block-rows of W and appends their descriptors and window records to the plan being
+// staged (`words` = its length so far, 64-word aligned on return); leaves W->grp_n = 0 when the shape is not
+// the kernel's or no block-row is long enough.  group_plan_words: what the workspace must hold for it.
 void build_group_plan(bsr_matrix* W, const int32_t* index_pointer_host, const int32_t* block_indices_host, size_t* words);
-int build_group_table(const bsr_matrix* W, int n_sub, int cus_per_xcd, std::vector<int32_t>& host);
 size_t group_plan_words(int64_t R, int32_t bs_r, int32_t bs_c, int64_t nnzb);
-size_t group_table_words(int64_t R, int32_t bs_r, int32_t bs_c);
 bsr_status launch_mfma_stripe(const spmm_args& a, const tune_opts& t);
 bool mfma_stripe_supports(const bsr_matrix* W, int tm);   // 16x16 blocks, 16-bit type, tm rows of X fit in LDS
 bsr_status launch_mfma_thin(const spmm_args& a, const tune_opts& t);    // bs_r = 16, bs_c = 1, fp32; needs scratch

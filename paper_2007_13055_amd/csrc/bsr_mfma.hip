@@ -186,7 +186,21 @@ bsr_status launch_mfma(const spmm_args& a, const tune_opts& tune)
             if (t.a == 0) t.a = tall ? 1 : 2;
         }
     }
-    if (variant == 5) return launch_mfma_group(a, t);
+    if (variant == 5) {
+        // the grouped (longest) block-rows in one launch, the other slots through the tile kernel
+        if (!mfma_group_supports(a.W)) return launch_mfma_tile(a, t);   // no block-row long enough
+        const bsr_status st = launch_mfma_group(a, t);
+        if (st != BSR_OK) return st;
+        spmm_args rest = a;
+        rest.first_slot = a.W->grp_slots;
+        tune_opts tt = t;
+        tt.variant = 3;
+        tt.b = 0;
+        tt.nw = 0;
+        if (tt.mt == 0) tt.mt = 1;
+        if (tt.a == 0) tt.a = 2;
+        return launch_mfma_tile(rest, tt);
+    }
     if (variant == 2) return launch_mfma_ksplit(a, t);
     if (variant == 3) return launch_mfma_tile(a, t);
     if (variant == 4) return launch_mfma_stripe(a, t);

@@ -13,6 +13,8 @@
 // m-tile the block-rows come longest first.  Workgroups that run at the same time on one XCD then
 // share an X stripe of TM rows in that XCD's L2.  The few block-rows that are much longer than the
 // rest (the plan's long_rows) are started first for all m-tiles.
+#include <algorithm>
+
 #include "bsr_mfma_common.h"
 
 using namespace bsr_dev;
@@ -244,15 +246,18 @@ bsr_status launch_tile_shape(const spmm_args& a, const tune_opts& tune)
             const int n_tiles = (m + TM - 1) / TM;
             // groups: the long rows, then runs of slots holding about `target` stored blocks each
             // (a group's W: target * block bytes, chosen near 1.5 MB of the 4 MB L2)
+            // (slots before a.first_slot are left out: another kernel multiplies those block-rows)
             slot_groups groups{};
+            const int first = std::min(std::max(a.first_slot, 0), R);
+            if (first >= R) return BSR_OK;
             {
-                const int n_long = W->long_rows;
+                const int n_long = std::max(W->long_rows, first);
                 const size_t block_bytes = (size_t)BS_R * BS_C * sizeof(T);
                 int64_t target = tune.b > 0 ? tune.b : (int64_t)((3u << 19) / block_bytes);
                 if (target < 1) target = 1;
                 int g = 0;
-                groups.start[0] = 0;
-                if (n_long > 0) groups.start[++g] = n_long;
+                groups.start[0] = first;
+                if (n_long > first) groups.start[++g] = n_long;
                 int64_t acc_blocks = 0;
                 for (int s = n_long; s < R; ++s) {
                     acc_blocks += W->slot_blocks[(size_t)s];
@@ -262,7 +267,7 @@ bsr_status launch_tile_shape(const spmm_args& a, const tune_opts& tune)
                 groups.n = g;
                 for (int q = g + 1; q <= kMaxGroups; ++q) groups.start[q] = R;
             }
-            const int64_t blocks = (int64_t)((n_tiles + kXcds - 1) / kXcds) * kXcds * R;
+            const int64_t blocks = (int64_t)((n_tiles + kXcds - 1) / kXcds) * kXcds * (R - first);
             if (blocks >= ((int64_t)1 << 31) || blocks * 256 >= ((int64_t)1 << 32)) return BSR_ERR_SHAPE;
             const size_t lds_stage = (size_t)(TM + BS_R) * (BS_C * sizeof(T) + 16);
             const size_t lds_out = (size_t)TM * (BS_R * sizeof(O) + 16);

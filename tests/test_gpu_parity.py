@@ -465,12 +465,13 @@ def test_stripe_kernel_variant(oracle_mod, monkeypatch, extra, dtype, out):
 
 
 # ------------------------------------------------------------------ the row-group kernel (variant 5)
-@pytest.mark.parametrize("extra", ["", ",a=1", ",a=4", ",a=63"])
+@pytest.mark.parametrize("extra", ["", ",b=1", ",b=3", ",b=1,nw=1"])
 @pytest.mark.parametrize("dtype,out", [("f16", "f16"), ("bf16", "bf16"), ("f16", "f32"), ("bf16", "f32")])
 def test_group_kernel_variant(oracle_mod, monkeypatch, extra, dtype, out):
-    """variant 5: 64x64 blocks of a 16-bit type, groups of up to 8 block-rows walking the union of their
-    block-columns.  Long, short, single-block and empty block-rows, more block-rows than one group holds, steps
-    with 1 to 8 blocks, ragged m; a = CUs per XCD the workgroup table assumes (how groups are split along m)."""
+    """variant 5: 64x64 blocks of a 16-bit type; the longest block-rows in groups of up to 8 that walk the union
+    of their block-columns, the other block-rows through the tile kernel.  Long, short, single-block and empty
+    block-rows, more long rows than the groups hold, block-columns with 1 to 8 blocks, ragged m; b = fewest
+    blocks of a grouped row (default 8), nw = groups at most."""
     monkeypatch.setenv("BSR_SPMM_TUNE", "variant=5" + extra)
     cases = [(5, np.array([3, 0, 9, 1])),
              (64, np.array([12, 12, 11, 12, 10, 12, 12, 9, 1, 0, 2])),            # a heavy group with full steps
@@ -490,7 +491,7 @@ def test_group_kernel_variant(oracle_mod, monkeypatch, extra, dtype, out):
 def test_group_kernel_small_integers_bitwise_duplicates_and_order(oracle_mod, monkeypatch):
     """Exact data (any summation order gives the oracle's value bit for bit), with unsorted block-columns and a
     block-column stored twice in one block-row (two steps of the same column)."""
-    monkeypatch.setenv("BSR_SPMM_TUNE", "variant=5")
+    monkeypatch.setenv("BSR_SPMM_TUNE", "variant=5,b=1")
     p = wl.small_integer_problem(333, 12 * 64, 11 * 64, 64, 64, 0.5, seed=23, in_dtype="f16", out_dtype="f32", lo=-2, hi=2)
     Yo, So = oracle_of(oracle_mod, p)
     Yg, _ = gpu_product(p, path=MFMA)
