@@ -33,7 +33,7 @@ size_t item_table_bytes(int64_t R)
     return items * kRowDescWords * sizeof(int32_t);   // one table; the workspace holds kItemSlots of them
 }
 
-size_t plan_bytes(int64_t R, int64_t nnzb, int32_t bs_r, int32_t bs_c)
+size_t plan_bytes(int64_t R, int64_t nnzb, int32_t bs_r, int32_t bs_c, int64_t k)
 {
     // row order (4R bytes) + row descriptors + pair pointers (4R) + pair entries (16 bytes each, at
     // most nnzb/2 + kStripeChunkPairs per block-row), each part padded to 256 bytes, + the k-split
@@ -45,6 +45,8 @@ size_t plan_bytes(int64_t R, int64_t nnzb, int32_t bs_r, int32_t bs_c)
     size_t b = per_row * (size_t)R + 52 * (size_t)nnzb + 4096 + kItemSlots * item_table_bytes(R);
     // row-group kernel (64x64 blocks): its group descriptors and window records
     b += sizeof(int32_t) * group_plan_words(R, bs_r, bs_c, nnzb);
+    // thin blocks: the phase positions of every block-row
+    b += sizeof(int32_t) * thinrow_plan_words(R, k, bs_r, bs_c);
     return (b + 255) & ~(size_t)255;
 }
 
@@ -209,7 +211,7 @@ bsr_status bsr_workspace_size(int64_t n, int64_t k, int32_t bs_r, int32_t bs_c, 
     *bytes = 0;
     bsr_status st = check_shape(n, k, bs_r, bs_c, nnzb);
     if (st != BSR_OK) return st;
-    *bytes = plan_bytes(n / bs_r, nnzb, bs_r, bs_c);
+    *bytes = plan_bytes(n / bs_r, nnzb, bs_r, bs_c, k);
     return BSR_OK;
 }
 
@@ -230,7 +232,7 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
         ((uintptr_t)block_indices_dev & 3u) || ((uintptr_t)index_pointer_dev & 3u))
         return BSR_ERR_ALIGN;
     const int64_t R = n / bs_r;
-    if (workspace_bytes < plan_bytes(R, nnzb, bs_r, bs_c)) return BSR_ERR_WORKSPACE;
+    if (workspace_bytes < plan_bytes(R, nnzb, bs_r, bs_c, k)) return BSR_ERR_WORKSPACE;
 
     bsr_matrix* W = new (std::nothrow) bsr_matrix();
     if (!W) return BSR_ERR_HIP;
@@ -459,6 +461,7 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
         }
     }
     build_group_plan(W, index_pointer_host, block_indices_host, &words);
+    build_thinrow_plan(W, index_pointer_host, block_indices_host, &words);
     size_t upload_words = words;
     {   // the per-m tables sit behind everything else, 256-byte aligned
         W->item_desc = const_cast<int32_t*>(W->row_order) + words;
@@ -505,10 +508,12 @@ bsr_status bsr_query_path(const bsr_matrix* W, int64_t m, bsr_path* path_out)
     // Matrix-core tiles are at least 16 rows of X tall: below that most of a tile is padding and
     // the wavefront-reduction kernels (the paper's own regime, m <= 8) stream W once instead.
     // Thin 16x1 fp32 blocks take the matrix-core path when the caller has lent enough scratch for
-    // the transposed copy of X.
+    // the transposed copy of X, or when their block-rows are stored in block-column order (one launch,
+    // no scratch).
     if ((mfma_supports(W) || mfma_small_supports(W)) && m >= 16) *path_out = BSR_PATH_MFMA;
     else if (mfma_thin_supports(W) && m >= 32 && W->scratch && W->scratch_bytes >= mfma_thin_scratch_bytes(W, m))
         *path_out = BSR_PATH_MFMA;
+    else if (mfma_thinrow_supports(W) && m >= 16) *path_out = BSR_PATH_MFMA;   // no scratch: rows of X staged in LDS
     else *path_out = BSR_PATH_WAVE;
     return BSR_OK;
 }
@@ -578,7 +583,7 @@ bsr_status bsr_spmm_ex(const bsr_matrix* W, int64_t m, const void* X_dev, void* 
             if (it != W->tuned.end()) { path = it->second.path; t = it->second.opts; tuned = true; }
         }
         // a remembered thin-block choice needs its scratch still lent
-        if (tuned && path == BSR_PATH_MFMA && mfma_thin_supports(W) &&
+        if (tuned && path == BSR_PATH_MFMA && mfma_thin_supports(W) && !(t.variant == 2 && mfma_thinrow_supports(W)) &&
             (!W->scratch || W->scratch_bytes < mfma_thin_scratch_bytes(W, m))) tuned = false;
         if (!tuned) { bsr_query_path(W, m, &path); if (!t.from_env) t = tune_opts{}; }
     }
@@ -597,8 +602,10 @@ static std::vector<tuned_choice> tune_candidates(const bsr_matrix* W, int64_t m)
     };
     const bool thin = mfma_thin_supports(W);
     if (thin) {
+        if (mfma_thinrow_supports(W) && m >= 8)
+            for (int a : {1, 2}) add(BSR_PATH_MFMA, 2, 0, 0, a, 0);
         if (W->scratch && W->scratch_bytes >= mfma_thin_scratch_bytes(W, m) && m >= 16)
-            for (int a : {4, 6, 8, 10, 12, 14, 16}) add(BSR_PATH_MFMA, 0, 0, 0, a, 0);
+            for (int a : {4, 6, 8, 10, 12, 14, 16}) add(BSR_PATH_MFMA, 1, 0, 0, a, 0);
     } else if (mfma_small_supports(W)) {
         if (m >= 8)
             for (int nw : {2, 4, 8})

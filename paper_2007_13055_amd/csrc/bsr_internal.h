@@ -28,6 +28,8 @@ constexpr int kItemSlots = 4;                     // k-split work-item tables a 
 //            per wavefront; ksplit: 1 = 16-row, 2 = 32-row tiles)
 //   a, b     per-variant: ksplit a = blocks per wavefront; tile a = blocks in flight, b-1 = long rows
 //            started first; stripe a = block-row groups; thin a = groups of 4 blocks in flight
+//            thin blocks: variant 1 = transposed copy in scratch + gather, 2 = rows of X staged in LDS
+//            (a = slots per wavefront)
 struct tune_opts {
     int variant = 0, nw = 0, mt = 0, a = 0, b = 0;
     bool from_env = false;                   // BSR_SPMM_TUNE is set: it overrides what bsr_tune() remembered
@@ -88,6 +90,11 @@ struct bsr_matrix {
     const int32_t* grp_recs = nullptr;       // device
     std::vector<int32_t> grp_host;           // host copy of both (descriptors first), for the plan checker
     size_t grp_host_recs_at = 0;             // word offset of the records in grp_host
+    // Thin blocks (16x1 fp32) whose block-rows store their blocks in non-decreasing block-column order
+    // (bsr_mfma_thinrow.hip): per slot the stored-block positions where the block-columns cross the multiples
+    // of 1024, [R][thin_nph + 1] (device); null when the kernel cannot take this W.
+    const int32_t* thin_ph = nullptr;
+    int32_t thin_nph = 0;
     int n_cu = 256;                          // CUs of the device the handle was created on (entry b of a table runs on CU b mod n_cu)
     int device = 0;                          // that device
     tune_opts env_tune;                      // BSR_SPMM_TUNE as it was when the handle was created
@@ -193,6 +200,11 @@ bsr_status launch_mfma_thin_static(const spmm_args& a, const tune_opts& t);
 // Resolves the built-in scratch array's device address for the current device (once per device).
 bsr_status mfma_thin_static_scratch(void** out);
 bool mfma_thin_supports(const bsr_matrix* W);
+// The same product in one launch, rows of X staged in LDS (no scratch): needs sorted block-rows, k % 4 == 0
+bsr_status launch_mfma_thinrow(const spmm_args& a, const tune_opts& t);
+bool mfma_thinrow_supports(const bsr_matrix* W);
+void build_thinrow_plan(bsr_matrix* W, const int32_t* index_pointer_host, const int32_t* block_indices_host, size_t* words);
+size_t thinrow_plan_words(int64_t R, int64_t k, int32_t bs_r, int32_t bs_c);
 bsr_status launch_mfma_small(const spmm_args& a, const tune_opts& t);   // bs_r, bs_c in {8,16}, not both 16
 bool mfma_small_supports(const bsr_matrix* W);
 size_t mfma_thin_scratch_bytes(const bsr_matrix* W, int64_t m);   // bytes of the transposed copy of X

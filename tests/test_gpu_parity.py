@@ -520,13 +520,79 @@ def test_group_kernel_config5_sampled_rows(oracle_mod, monkeypatch):
     assert np.array_equal(wl.round_to_storage(Yg32.astype(np.float32), "f16").astype(np.float64), Yg)
 
 
+@pytest.mark.parametrize("u", ["", "a=1", "a=2", "auto"])
+def test_thin_rows_staged_in_lds(oracle_mod, monkeypatch, u):
+    """16x1 fp32 blocks on the matrix-core path in one launch: rows of X staged in LDS 1024 columns at a time,
+    the gather of columns done there (a = slots per multiplying wavefront).  One to five phases, a last phase
+    that is not full, block-rows with none, one, and several chunks of 32 blocks in a phase, ragged m, fewer
+    block-rows than a workgroup takes; no scratch is lent."""
+    import torch
+    import paper_2007_13055_amd as lib
+    path = MFMA
+    if u == "auto":
+        path = 0                                                   # no knob, nothing lent: the library's own choice
+    else:
+        monkeypatch.setenv("BSR_SPMM_TUNE", "variant=2" + ("," + u if u else ""))
+    for m, R, C in ((16, 3, 40), (70, 9, 132), (257, 20, 300), (64, 5, 8), (600, 11, 64), (48, 10, 2500), (33, 70, 4096),
+                    (17, 4, 5000)):
+        rng = np.random.default_rng(m + R)
+        counts = rng.integers(0, min(C, 400) + 1, size=R)
+        counts[0] = 0
+        counts[-1] = min(C, 377)
+        counts[R // 2] = 1
+        p = wl.make_problem("thin", m, C, R * 16, 16, 1, "f32", "f32", ("counts", counts), ("uniform", 1.0),
+                            ("uniform", 1.0), 700 + m)
+        Yo, So = oracle_of(oracle_mod, p)
+        W = lib.bsr_create(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype="f32")
+        assert lib.bsr_query_path(W, m) == MFMA                    # without any scratch
+        assert lib.bsr_query_path(W, 8) == WAVE
+        X = to_device(p.X, "f32")
+        Y = torch.full((m, p.n), float("nan"), device="cuda")
+        st = lib.load_library().bsr_spmm_ex(W.handle, m, X.data_ptr(), Y.data_ptr(), 0, path,
+                                            torch.cuda.current_stream().cuda_stream)
+        assert st == 0
+        torch.cuda.synchronize()
+        Yg = Y.double().cpu().numpy()
+        check(Yg, Yo, So, p.tau, f"thin rows-in-LDS {u} m={m} R={R} C={C}")
+        Y.fill_(float("nan"))
+        st = lib.load_library().bsr_spmm_ex(W.handle, m, X.data_ptr(), Y.data_ptr(), 0, path,
+                                            torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert st == 0 and np.array_equal(Y.double().cpu().numpy(), Yg), "two runs differ: race"
+
+
+def test_thin_rows_staged_in_lds_bitwise_and_fallback(oracle_mod):
+    """Exact data: the one-launch thin kernel gives the oracle's value bit for bit (duplicates of a block-column
+    included: they keep non-decreasing order).  A block-row stored out of order makes the plan leave the
+    kernel out: the product then needs the scratch again and still matches."""
+    import paper_2007_13055_amd as lib
+    p = wl.small_integer_problem(100, 2048 + 64, 9 * 16, 16, 1, 0.3, seed=31)
+    Yo, So = oracle_of(oracle_mod, p)
+    Yg, W = gpu_product(p, path=MFMA)
+    assert np.array_equal(Yg, Yo)
+    rng = np.random.default_rng(32)
+    ptr = np.array([0, 5, 5, 9], dtype=np.int32)
+    idx = np.array([1, 1, 3, 3, 7, 0, 2, 2, 6], dtype=np.int32)
+    data = rng.integers(-3, 4, size=(9, 16, 1)).astype(np.float32)
+    X = rng.integers(-3, 4, size=(40, 8)).astype(np.float32)
+    q = wl.Problem("dup", 40, 8, 48, 16, 1, "f32", "f32", X, data, idx, ptr)
+    Yo, So = oracle_of(oracle_mod, q)
+    Yg, Wq = gpu_product(q, path=MFMA)
+    assert np.array_equal(Yg, Yo)
+    idx2 = idx.copy(); idx2[[0, 4]] = idx2[[4, 0]]; data2 = data.copy(); data2[[0, 4]] = data2[[4, 0]]   # same matrix, row 0 out of order
+    q2 = wl.Problem("unsorted", 40, 8, 48, 16, 1, "f32", "f32", X, data2, idx2, ptr)
+    W2 = lib.bsr_create(q2.n, q2.k, q2.block_data, q2.block_indices, q2.index_pointer, dtype="f32")
+    assert lib.bsr_query_path(W2, 40) == WAVE                      # no scratch lent, kernel not available
+    Yg2, _ = gpu_product(q2, path=MFMA, W=W2)                      # the binding lends the scratch
+    assert np.array_equal(Yg2, Yo)
+
+
 @pytest.mark.parametrize("u", ["", "a=4", "a=8", "a=16", "a=6,b=1", "a=10,b=2", "b=4", "a=14,b=8"])
 def test_thin_mfma_path(oracle_mod, monkeypatch, u):
-    """16x1 fp32 blocks on the matrix-core path: transposed copy of X in lent scratch, then gather + MFMA
-    (a = groups of 4 blocks per chunk, b = m-tile groups over the XCDs)."""
+    """16x1 fp32 blocks on the matrix-core path with a transposed copy of X in lent scratch (variant 1), then
+    gather + MFMA (a = groups of 4 blocks per chunk, b = m-tile groups over the XCDs)."""
     import paper_2007_13055_amd as lib
-    if u:
-        monkeypatch.setenv("BSR_SPMM_TUNE", u)
+    monkeypatch.setenv("BSR_SPMM_TUNE", "variant=1" + ("," + u if u else ""))
     for m, R, C in ((32, 3, 40), (70, 9, 130), (257, 20, 300), (64, 5, 7), (600, 11, 64)):
         rng = np.random.default_rng(m + R)
         counts = rng.integers(0, min(C, 90) + 1, size=R)
@@ -548,7 +614,10 @@ def test_thin_mfma_needs_scratch():
     import torch
     import paper_2007_13055_amd as lib
     p = wl.make_problem("thin", 64, 64, 64, 16, 1, "f32", "f32", ("bernoulli", 0.3), ("uniform", 1.0), ("uniform", 1.0), 9)
-    W = lib.bsr_create(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype="f32")
+    # every block-row stored in descending block-column order: the one-launch kernel (which needs no scratch)
+    # is not available, the matrix-core path is the one with the transposed copy
+    order = np.concatenate([np.arange(p.index_pointer[r], p.index_pointer[r + 1])[::-1] for r in range(4)])
+    W = lib.bsr_create(p.n, p.k, p.block_data[order], p.block_indices[order], p.index_pointer, dtype="f32")
     assert lib.bsr_query_path(W, 64) == WAVE                      # nothing lent yet: wave path
     so = lib.load_library()
     X = to_device(p.X, "f32")

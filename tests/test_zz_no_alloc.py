@@ -22,10 +22,13 @@ def _static_product(so, W, X, m, n):
     return Y
 
 
-def test_static_scratch_product_matches_lent_scratch_product(oracle_mod):
+def test_static_scratch_product_matches_lent_scratch_product(oracle_mod, monkeypatch):
     import torch
     import paper_2007_13055_amd as lib
     so = lib.load_library()
+    # bsr_spmm_ex on the matrix-core path would by itself take the one-launch kernel that needs no scratch;
+    # variant 1 is the product with the transposed copy of X in lent scratch, whose kernels bsr_spmm_static runs
+    monkeypatch.setenv("BSR_SPMM_TUNE", "variant=1")
     # the thin workload at full size (4 MiB + 256 bytes of the 8 MiB array), then a smaller, ragged one
     big = wl.config(4)
     rng = np.random.default_rng(44)
