@@ -22,6 +22,14 @@
  *   - dense matrices are row-major and contiguous; index arrays are int32;
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream);
  *     device work is queued on it and the call returns without waiting.
+ *
+ * Debug mode.  A handle created while the environment variable BSR_SPMM_DEBUG is set to anything but "0"
+ * re-checks, on the device and before every product (bsr_spmm, bsr_spmm_ex, bsr_spmm_static, bsr_sddmm),
+ * the arrays every kernel address derives from: index_pointer and block_indices as they are in device
+ * memory at that moment (BSR_ERR_INDPTR, BSR_ERR_INDEX) and the plan in the workspace
+ * (BSR_ERR_WORKSPACE when it no longer holds what bsr_create() wrote).  On a failure nothing else is
+ * launched.  The check waits for the stream (one extra launch, a 16-byte copy, a synchronisation), so
+ * such a call is NOT asynchronous; it is skipped while the stream is being captured into a graph.
  */
 #ifndef BSR_SPMM_H
 #define BSR_SPMM_H

@@ -47,6 +47,7 @@ size_t plan_bytes(int64_t R, int64_t nnzb, int32_t bs_r, int32_t bs_c, int64_t k
     b += sizeof(int32_t) * group_plan_words(R, bs_r, bs_c, nnzb);
     // thin blocks: the phase positions of every block-row
     b += sizeof(int32_t) * thinrow_plan_words(R, k, bs_r, bs_c);
+    b += 256;                                         // debug mode's result words
     return (b + 255) & ~(size_t)255;
 }
 
@@ -467,10 +468,18 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
         W->item_desc = const_cast<int32_t*>(W->row_order) + words;
         W->item_capacity = item_table_bytes(R) / (kRowDescWords * sizeof(int32_t));
         words += kItemSlots * W->item_capacity * kRowDescWords;
+        W->debug_out = const_cast<int32_t*>(W->row_order) + words;
+        words += 64;
     }
     // the plan must fit what bsr_workspace_size promised (its bound is per block-row and per stored block)
     if (sizeof(int32_t) * words > workspace_bytes) { delete W; return BSR_ERR_WORKSPACE; }
     words = upload_words;
+    {
+        const char* dbg = std::getenv("BSR_SPMM_DEBUG");
+        W->debug = dbg && dbg[0] && dbg[0] != '0';
+        W->debug_words = words;
+        if (W->debug) W->debug_sum = debug_plan_sum(W->staging.data(), words);
+    }
     if (R > 0) {
         hipError_t e = hipMemcpyAsync(workspace_dev, W->staging.data(), sizeof(int32_t) * words,
                                       hipMemcpyHostToDevice, (hipStream_t)hip_stream);
@@ -554,6 +563,10 @@ bsr_status check_product_args(const bsr_matrix* W, int64_t m, const void* X_dev,
 bsr_status run_product(const spmm_args& a, bsr_path path, const tune_opts& t)
 {
     order_after_upload(a.stream, a.W->plan_uploaded, a.W->plan_landed);
+    if (a.W->debug) {
+        const bsr_status dbg = debug_check_device_arrays(a.W, a.stream);
+        if (dbg != BSR_OK) return dbg;
+    }
     // no stored block (k == 0 included): every kernel family would only store zeros; the wavefront
     // kernels do that for any shape without touching X or W
     if (a.W->nnzb == 0) return launch_wave(a, t);
@@ -708,6 +721,10 @@ bsr_status bsr_spmm_static(const bsr_matrix* W, int64_t m, const void* X_dev, vo
     const spmm_args a{W, m, X_dev, Y_dev, y_dtype, (hipStream_t)hip_stream};
     if (mfma_thin_scratch_bytes(W, m) > (size_t)BSR_STATIC_SCRATCH_BYTES) return BSR_ERR_SCRATCH_LIMIT;
     order_after_upload(a.stream, W->plan_uploaded, W->plan_landed);
+    if (W->debug) {
+        const bsr_status dbg = debug_check_device_arrays(W, a.stream);
+        if (dbg != BSR_OK) return dbg;
+    }
     tune_opts t = W->env_tune;
     if (W->nnzb == 0) return launch_wave(a, t);
     return launch_mfma_thin_static(a, t);

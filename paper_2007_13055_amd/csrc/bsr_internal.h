@@ -6,6 +6,7 @@
 #include <atomic>
 #include <cstddef>
 #include <cstdint>
+#include <cstring>
 #include <functional>
 #include <map>
 #include <mutex>
@@ -95,6 +96,11 @@ struct bsr_matrix {
     // of 1024, [R][thin_nph + 1] (device); null when the kernel cannot take this W.
     const int32_t* thin_ph = nullptr;
     int32_t thin_nph = 0;
+    // Debug mode (BSR_SPMM_DEBUG=1 at bsr_create, bsr_debug.hip): the device arrays are re-checked before every product
+    bool debug = false;
+    size_t debug_words = 0;                  // words of the plan that never change after bsr_create
+    uint64_t debug_sum = 0;                  // their position-weighted sum
+    int32_t* debug_out = nullptr;            // device, 4 words behind everything else in the workspace
     int n_cu = 256;                          // CUs of the device the handle was created on (entry b of a table runs on CU b mod n_cu)
     int device = 0;                          // that device
     tune_opts env_tune;                      // BSR_SPMM_TUNE as it was when the handle was created
@@ -146,6 +152,10 @@ struct spmm_args {
 };
 
 tune_opts read_tune_env();
+// Debug mode: checks index_pointer, block_indices and the plan on the device (one launch, a copy and a stream
+// synchronisation); BSR_OK when the handle is not in debug mode or the stream is being captured.
+bsr_status debug_check_device_arrays(const bsr_matrix* W, hipStream_t stream);
+uint64_t debug_plan_sum(const int32_t* words, size_t n);
 
 // Stored blocks of one block-row that a workgroup of the sampled product takes together (they share
 // the piece of G): 4 while a block is at most 2 KiB, else 2.

@@ -792,6 +792,10 @@ extern "C" bsr_status bsr_sddmm(const bsr_matrix* W, int64_t m, const void* G_de
     if (((uintptr_t)G_dev | (uintptr_t)X_dev | (uintptr_t)D_dev) & 15u) return BSR_ERR_ALIGN;
     hipStream_t stream = (hipStream_t)hip_stream;
     order_after_upload(stream, W->plan_uploaded, W->plan_landed);
+    if (W->debug) {
+        const bsr_status dbg = debug_check_device_arrays(W, stream);
+        if (dbg != BSR_OK) return dbg;
+    }
     // m == 0 needs no special case: the kernels then read nothing and store zeros (an empty sum)
     const int mi = (int)m;
     if (W->dtype == BSR_F32) return launch_sddmm_types<float, float>(W, mi, G_dev, X_dev, D_dev, stream);

@@ -889,3 +889,48 @@ def test_sampled_product_small_integers_bitwise(oracle_mod):
     D = lib.bsr_sddmm(W, to_device(G, "f16"), to_device(p.X, "f16"), d_dtype="f32")
     torch.cuda.synchronize()
     assert np.array_equal(D.double().cpu().numpy(), Do)
+
+
+def test_debug_mode_checks_device_arrays_before_every_product(oracle_mod, monkeypatch):
+    """BSR_SPMM_DEBUG=1: a block-column, an index_pointer entry or a plan word damaged in device memory after
+    bsr_create is reported by the next product (INDEX, INDPTR, WORKSPACE) and nothing is launched on the damaged
+    arrays; once repaired the product is the oracle's again."""
+    import torch
+    import paper_2007_13055_amd as lib
+    monkeypatch.setenv("BSR_SPMM_DEBUG", "1")
+    p = wl.make_problem("dbg", 70, 256, 192, 32, 32, "f16", "f16", ("bernoulli", 0.5), ("normal", 1.0), ("normal", 1.0), 77)
+    Yo, So = oracle_of(oracle_mod, p)
+    W = lib.bsr_create(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype="f16")
+    so = lib.load_library()
+    X = to_device(p.X, "f16")
+    Y = torch.full((p.m, p.n), 7.0, dtype=torch.float16, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def product():
+        st = so.bsr_spmm_ex(W.handle, p.m, X.data_ptr(), Y.data_ptr(), 1, 0, stream)
+        torch.cuda.synchronize()
+        return st
+
+    assert product() == 0
+    check(Y.double().cpu().numpy(), Yo, So, p.tau, "debug mode, intact arrays", out_dtype="f16")
+    idx, ptr, ws = W._tensors[1], W._tensors[2], W._tensors[3]
+    for tensor, pos, bad, code in ((idx, 3, p.k // 32, 4), (idx, 0, -1, 4), (ptr, 2, 10 ** 6, 3), (ptr, 0, 1, 3)):
+        Y.fill_(7.0)
+        keep = int(tensor[pos])
+        tensor[pos] = bad
+        assert product() == code
+        assert torch.all(Y == 7.0), "a product ran on damaged arrays"
+        tensor[pos] = keep
+    words = ws.view(torch.int32)
+    keep = int(words[5])
+    words[5] = keep ^ 1                                            # a word of the plan (the slot order)
+    Y.fill_(7.0)
+    assert product() == 7 and torch.all(Y == 7.0)
+    words[5] = keep
+    assert product() == 0
+    check(Y.double().cpu().numpy(), Yo, So, p.tau, "debug mode, repaired arrays", out_dtype="f16")
+    G = to_device(np.zeros((p.m, p.n), dtype=np.float32), "f16")
+    idx[1] = -5
+    D = torch.zeros((p.nnzb, 32, 32), dtype=torch.float16, device="cuda")
+    assert so.bsr_sddmm(W.handle, p.m, G.data_ptr(), X.data_ptr(), D.data_ptr(), 1, stream) == 4
+    idx[1] = int(p.block_indices[1])
