@@ -39,6 +39,7 @@ WORKLOAD_TEXT = {
               "block-row by rank power law s=1.2; N(0,0.02); Y fp16",
 }
 CONFIG_ID = {"tiny": 1, "ffn": 2, "batched": 3, "thin": 4, "skewed": 5}
+RAMP_S = 0.03                                        # untimed replays of the timed launches before every timed region
 
 
 def _graph_chunk(steps, limit):
@@ -98,6 +99,12 @@ def _time_steps(fn, steps, warmup, graph_chunk):
         def run():
             for _ in range(steps):
                 fn()
+    # untimed ramp: a short region after an idle spell runs at lower clocks (20 launches of the largest
+    # workload: 157 instead of 137 us per launch), so the same launches are replayed for RAMP_S seconds first
+    t_ramp = time.perf_counter()
+    while time.perf_counter() - t_ramp < RAMP_S:
+        run()
+        torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -365,6 +372,7 @@ def main():
     out = {
         "metric": "effective TFLOP/s of bsr_spmm (2*m*nnzb*bs_r*bs_c per call)",
         "value": p.flops / sec / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ramp_ms": RAMP_S * 1e3,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": p.in_dtype, "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[p.name],
