@@ -142,10 +142,36 @@ def _roofline(p, sec_per_launch):
     return {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, **both}
 
 
+ROW_SUBSET = None                                    # --row-subset: ("longest" | "rest", N), analysis only
+
+
+def _row_subset(p, which, count):
+    """The workload with only its `count` longest block-rows ("longest") or all but those ("rest") keeping
+    their stored blocks; the others become empty block-rows (their columns of Y are still written).  An analysis
+    aid: which block-rows a kernel's time and traffic come from."""
+    import numpy as np
+    ptr = p.index_pointer.astype(np.int64)
+    counts = np.diff(ptr)
+    longest = np.argsort(-counts, kind="stable")[:count]
+    keep = np.zeros(counts.shape[0], dtype=bool)
+    keep[longest] = True
+    if which == "rest":
+        keep = ~keep
+    sel = np.concatenate([np.arange(ptr[r], ptr[r + 1]) for r in range(counts.shape[0]) if keep[r]]
+                         + [np.zeros(0, dtype=np.int64)]).astype(np.int64)
+    new_ptr = np.zeros(counts.shape[0] + 1, dtype=np.int32)
+    np.cumsum(np.where(keep, counts, 0), out=new_ptr[1:])
+    p.block_indices, p.block_data, p.index_pointer = p.block_indices[sel].copy(), p.block_data[sel].copy(), new_ptr
+    p.note = f"{which} {count} block-rows only"
+    return p
+
+
 def _bench_config(cid, steps, warmup, graph_chunk):
     import workloads as wl
     import paper_2007_13055_amd as lib
     p = wl.config(cid)
+    if ROW_SUBSET:
+        p = _row_subset(p, *ROW_SUBSET)
     W, X, Y = _upload(p)
     fn = lambda: lib.bsr_spmm(W, X, Y)
     wall, ev, mode = _time_steps(fn, steps, warmup, graph_chunk)
@@ -338,6 +364,8 @@ def main():
                     help="also time the 36 cells of the paper's own shape grid (m = 1, 8) and add them as 'paper_grid'")
     ap.add_argument("--workload", default="skewed", choices=list(CONFIG_ID),
                     help="workload of the headline line (default: the largest, 'skewed')")
+    ap.add_argument("--row-subset", default="", metavar="longest:N|rest:N",
+                    help="analysis: keep only the N longest block-rows of the headline workload, or all but those")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run 20 device-to-device copies of this many MiB and exit: the reference a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE reading is scaled by")
@@ -347,6 +375,13 @@ def main():
                  "block-rows of W and rows of X both split without one). Use --gpus 1.")
     if a.steps < 1 or a.warmup < 0:
         sys.exit("bench.py: --steps must be at least 1 and --warmup non-negative")
+    if a.row_subset:
+        global ROW_SUBSET
+        which, _, count = a.row_subset.partition(":")
+        if which not in ("longest", "rest") or not count.isdigit():
+            sys.exit("bench.py: --row-subset takes longest:N or rest:N")
+        ROW_SUBSET = (which, int(count))
+        a.no_all_configs = True                      # the subset applies to the headline workload only
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")

@@ -77,17 +77,17 @@ __device__ __forceinline__ void wait_vm()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// Returns when at most the loads of `tiles` tiles (one per tile and wavefront, the youngest) are still in flight.
+// Returns when at most the loads of `tiles` tiles (two per tile and moving wavefront, the youngest) are still in flight.
 __device__ __forceinline__ void wait_all_but_tiles(int tiles)
 {
     switch (tiles) {
         case 0: wait_vm<0>(); break;
-        case 1: wait_vm<1>(); break;
-        case 2: wait_vm<2>(); break;
-        case 3: wait_vm<3>(); break;
-        case 4: wait_vm<4>(); break;
-        case 5: wait_vm<5>(); break;
-        default: wait_vm<6>(); break;
+        case 1: wait_vm<2>(); break;
+        case 2: wait_vm<4>(); break;
+        case 3: wait_vm<6>(); break;
+        case 4: wait_vm<8>(); break;
+        case 5: wait_vm<10>(); break;
+        default: wait_vm<12>(); break;
     }
 }
 
@@ -124,7 +124,7 @@ struct out_geom {
 };
 
 template <typename T, typename O>
-__global__ __launch_bounds__(512) void bsr_mfma_group(const T* __restrict__ X, const T* __restrict__ data,
+__global__ __launch_bounds__(768) void bsr_mfma_group(const T* __restrict__ X, const T* __restrict__ data,
                                                       const int32_t* __restrict__ recs,
                                                       const int32_t* __restrict__ gdesc, O* __restrict__ Y,
                                                       int m, int k, int n, int n_groups, int n_sub)
@@ -135,14 +135,14 @@ __global__ __launch_bounds__(512) void bsr_mfma_group(const T* __restrict__ X, c
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     unsigned char* const ring = lds + kRecBytes;      // records first, then the ring of tiles
 
-    // 8 wavefronts, two per SIMD (one wavefront alone issues an instruction every 4 cycles at best, and the
-    // bookkeeping of the tile stream is some 20 instructions per tile): wavefronts 0-3 take the group's
-    // rows 0-3, wavefronts 4-7 its rows 4-7, each a quadrant of every block product of its rows; all
-    // eight move an eighth (8 rows) of every tile.
+    // 12 wavefronts, three per SIMD.  Wavefront j < 8 multiplies the group's row j (the rows come longest
+    // first); wavefronts 8-11 only move tiles, each a quarter (16 rows) of every tile: a wavefront that
+    // issues loads waits for the memory pipeline to take them (about 100 cycles per 1 KiB load while a
+    // window streams in), and a wavefront that multiplied as well would be the last at every barrier.
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int half = wave >> 2, cw = wave & 3;
-    const int wm = cw >> 1, wn = cw & 1;              // the wavefront's quadrant: rows of X, rows of the block
+    const bool producer = wave >= kG;
+    const int pq = wave & 3;
 
     // workgroup -> (64-row sub-tile of X, group): XCD x (which receives the workgroups b = x mod 8) takes the
     // sub-tiles x, x+8, ..., and the groups of a sub-tile follow each other on that XCD, so the second
@@ -157,126 +157,142 @@ __global__ __launch_bounds__(512) void bsr_mfma_group(const T* __restrict__ X, c
     const int n_win = gd[9];
     const int32_t* __restrict__ rec = recs + (size_t)gd[8] * kRec;
 
-    // ---- moving tiles: wavefront q takes rows 8q .. 8q+7 of every tile, one 1 KiB load ----
-    // lane l moves the 16 bytes at piece position l mod 8 of row 8q + l div 8, which hold the row's
-    // piece (position ^ row mod 8)
+    // ---- moving tiles: wavefront 4+q takes rows 16q .. 16q+15 of every tile, two 1 KiB loads ----
+    // load i covers rows 16q + 8i .. +7: lane l moves the 16 bytes at piece position l mod 8 of row
+    // 16q + 8i + l div 8, which hold the row's piece (position ^ row mod 8)
     const unsigned char* Xb = reinterpret_cast<const unsigned char*>(X);
     const unsigned char* Wb = reinterpret_cast<const unsigned char*>(data);
     const int lrow = lane >> 3;
     const unsigned piece = (unsigned)((lane & 7) ^ lrow) * 16u;
     const unsigned row_bytes = (unsigned)k * (unsigned)sizeof(T);
-    // byte offset of the lane's piece (m*k*2 < 2^32); rows past m repeat row m-1, their results are never stored
-    const int prow = 8 * wave + lrow;
-    const unsigned x_off = (unsigned)min(sub * kSub + prow, m - 1) * row_bytes + piece;
-    const unsigned w_off = (unsigned)prow * 128u + piece;
+    // byte offsets of the lane's two pieces (m*k*2 < 2^32); rows past m repeat row m-1, their results are never stored
+    const int prow0 = 16 * pq + lrow, prow1 = prow0 + 8;
+    const unsigned x_off0 = (unsigned)min(sub * kSub + prow0, m - 1) * row_bytes + piece;
+    const unsigned x_off1 = (unsigned)min(sub * kSub + prow1, m - 1) * row_bytes + piece;
+    const unsigned w_off0 = (unsigned)prow0 * 128u + piece, w_off1 = (unsigned)prow1 * 128u + piece;
     // Window w lives in the kWin slots starting at slot (w mod 3) * kWin, tile i in the i-th of them.
     // A window's record is read from LDS one word per lane (rv: lanes 16q .. 16q+15 hold record w+q) and
     // its words are taken out with lane reads; `at` = lane of the record's word 0.
     auto issue = [&](int rv, int at, int w3) __attribute__((always_inline)) {   // the tiles of one window
         const int nt = __builtin_amdgcn_readlane(rv, at + 1) & 15;
-        unsigned char* dst = ring + w3 * (kWin * kTileBytes) + wave * 1024;
+        unsigned char* dst = ring + w3 * (kWin * kTileBytes) + pq * 2048;
         for (int i = 0; i < nt; ++i, dst += kTileBytes) {
             const int code = __builtin_amdgcn_readlane(rv, at + kRecTilesAt + i);
-            if (code < 0)                             // X tile of a block-column
-                __builtin_amdgcn_global_load_lds((glob_void*)(Xb + (size_t)(code & 0x7fffffff) * 128u + x_off), (lds_void*)dst, 16, 0, 0);
-            else                                      // a stored block
-                __builtin_amdgcn_global_load_lds((glob_void*)(Wb + (size_t)code * (size_t)kTileBytes + w_off), (lds_void*)dst, 16, 0, 0);
+            if (code < 0) {                           // X tile of a block-column
+                const unsigned char* base = Xb + (size_t)(code & 0x7fffffff) * 128u;
+                __builtin_amdgcn_global_load_lds((glob_void*)(base + x_off0), (lds_void*)dst, 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((glob_void*)(base + x_off1), (lds_void*)(dst + 1024), 16, 0, 0);
+            } else {                                  // a stored block
+                const unsigned char* base = Wb + (size_t)code * (size_t)kTileBytes;
+                __builtin_amdgcn_global_load_lds((glob_void*)(base + w_off0), (lds_void*)dst, 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((glob_void*)(base + w_off1), (lds_void*)(dst + 1024), 16, 0, 0);
+            }
         }
     };
-    // 64 records (4 KiB) into their half of the record area, 1 KiB per wavefront of the first four; pieces
-    // past the group's last record repeat its last piece (never used)
+    // 64 records (4 KiB) into their half of the record area, 1 KiB per moving wavefront; pieces past the
+    // group's last record repeat its last piece (never used)
     const int last_piece = n_win * (kRec / 4) - 1;
     auto load_records = [&](int chunk) __attribute__((always_inline)) {
-        if (half == 0) {
-            const int pc = min(chunk * 256 + cw * 64 + lane, last_piece);
-            __builtin_amdgcn_global_load_lds((glob_void*)(reinterpret_cast<const unsigned char*>(rec) + (size_t)pc * 16),
-                                             (lds_void*)(lds + (chunk & 1) * (kRecBytes / 2) + cw * 1024), 16, 0, 0);
-        }
+        const int pc = min(chunk * 256 + pq * 64 + lane, last_piece);
+        __builtin_amdgcn_global_load_lds((glob_void*)(reinterpret_cast<const unsigned char*>(rec) + (size_t)pc * 16),
+                                         (lds_void*)(lds + (chunk & 1) * (kRecBytes / 2) + pq * 1024), 16, 0, 0);
     };
     auto read_records = [&](int w) -> int {           // lane l: word l mod 16 of record w + l div 16
         const int q = (w + (lane >> 4)) & (kRecLds - 1);
         return *reinterpret_cast<const int*>(lds + q * (kRec * 4) + (lane & 15) * 4);
     };
 
-    // ---- multiplying wavefronts ----
+    // ---- multiplying: a whole 64x64 block per wavefront ----
     // operand of a 16x16x32 MFMA: lane l supplies row (l mod 16) of its 16-row tile, k elements
-    // 32*ks + 8*(l div 16) .. +7 = piece 4*ks + l div 16 of the row; ks = 1 differs by XOR 64 bytes
+    // 32*ks + 8*(l div 16) .. +7 = piece 4*ks + l div 16 of the row; ks = 1 differs by XOR 64 bytes.
+    // A wavefront keeps the operands of one k half of a block at a time (4 tiles of the block, 4 of X):
+    // while one half is multiplied (16 MFMAs on 16 accumulators) the same half of the next block is read.
     const int fr = lane & 15, fq = lane >> 4;
     const unsigned f_off = (unsigned)fr * 128u + (unsigned)((fq ^ (fr & 7)) * 16);
-    const unsigned xf_off = (unsigned)(32 * wm) * 128u + f_off;
-    const unsigned wf_off = (unsigned)(32 * wn) * 128u + f_off;
-
-    constexpr int kHalfRows = kG / 2;
-    f32x4 acc[kHalfRows][2][2];
+    struct half_frag {
+        u32x4 w[4], x[4];
+        __device__ __forceinline__ void load(const unsigned char* wt, const unsigned char* xt, unsigned off)
+        {
 #pragma unroll
-    for (int j = 0; j < kHalfRows; ++j)
+            for (int t = 0; t < 4; ++t) w[t] = *reinterpret_cast<const u32x4*>(wt + off + t * 2048u);
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
+            for (int t = 0; t < 4; ++t) x[t] = *reinterpret_cast<const u32x4*>(xt + off + t * 2048u);
+        }
+    };
+    f32x4 acc[4][4];                                  // [16 rows of the block][16 rows of X]
 #pragma unroll
-            for (int rt = 0; rt < 2; ++rt) acc[j][ct][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) acc[ct][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto multiply = [&](const half_frag& f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt) acc[ct][rt] = mfma16<T>(f.w[ct], f.x[rt], acc[ct][rt]);
+    };
 
     // the first 128 records, then windows 0 and 1, are on their way before the loop
-    load_records(0);
-    if (n_win > 64) load_records(1);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (producer) {
+        load_records(0);
+        if (n_win > 64) load_records(1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
     barrier();
     int rv = read_records(0);
-    issue(rv, 0, 0);
-    if (n_win > 1) issue(rv, 16, 1);
+    if (producer) {
+        issue(rv, 0, 0);
+        if (n_win > 1) issue(rv, 16, 1);
+    }
 
     int w3 = 0;                                       // w mod 3
     for (int w = 0; w < n_win; ++w) {
-        const int next_tiles = w + 1 < n_win ? (__builtin_amdgcn_readlane(rv, 17) & 15) : 0;
-        wait_all_but_tiles(next_tiles);               // this wavefront's share of window w has landed
+        if (producer) {
+            const int next_tiles = w + 1 < n_win ? (__builtin_amdgcn_readlane(rv, 17) & 15) : 0;
+            wait_all_but_tiles(next_tiles);           // this wavefront's share of window w has landed
+        }
         barrier();                                    // ... everybody's has, and everybody is done with window w-1
         const int rv_next = read_records(w + 1);      // used in the next trip
-        // every 64 windows the half of the record area that was used up takes the records 64 .. 127 ahead
-        // (loads complete in order, so they have landed, for everybody, many windows before they are read)
-        if ((w & 63) == 0 && w > 0 && w + 64 < n_win) load_records((w >> 6) + 1);
-        // window w+2 takes the slots of window w-1.  Wavefronts 0-3 issue its loads before they multiply,
-        // wavefronts 4-7 afterwards: while one half waits for the memory pipeline to take its loads the
-        // other half multiplies.
-        if (half == 0 && w + 2 < n_win) issue(rv, 32, w3 == 0 ? 2 : w3 - 1);
-
-        const int all_counts = __builtin_amdgcn_readlane(rv, 0), info = __builtin_amdgcn_readlane(rv, 1);
-        int xis = __builtin_amdgcn_readlane(rv, 2);
+        if (producer) {
+            // every 64 windows the half of the record area that was used up takes the records 64 .. 127 ahead
+            // (loads complete in order, so they have landed, for everybody, many windows before they are read)
+            if ((w & 63) == 0 && w > 0 && w + 64 < n_win) load_records((w >> 6) + 1);
+            if (w + 2 < n_win) issue(rv, 32, w3 == 0 ? 2 : w3 - 1);   // window w+2 takes the slots of window w-1
+        }
+        const unsigned all_counts = (unsigned)__builtin_amdgcn_readlane(rv, 0);
+        const int info = __builtin_amdgcn_readlane(rv, 1);
+        const unsigned xis = (unsigned)__builtin_amdgcn_readlane(rv, 2);
         const int nx = (info >> 4) & 15;
-        // this wavefront's rows: the low or the high 16 bits of the counts; the blocks of the rows before
-        // them (the window's blocks are sorted by row) are skipped
-        const int lo = all_counts & 0xffff;
-        const int before = half == 0 ? 0 : (lo & 15) + ((lo >> 4) & 15) + ((lo >> 8) & 15) + (lo >> 12);
-        const int counts = half == 0 ? lo : (int)((unsigned)all_counts >> 16);
-        xis = (int)((unsigned)xis >> (4 * before));
-        // The operands of the next stored block are read from LDS while the current one is multiplied;
-        // behind the last block that reads a slot nobody waits for, and drops it (the slot behind the
-        // ring's last window exists for this).
-        const unsigned char* wb = ring + w3 * (kWin * kTileBytes);
-        const unsigned char* wt = wb + (nx + before) * kTileBytes;   // tile of the block being read ahead
-        frag4 xn, wn4;
-        xn.load(wb + (xis & 15) * kTileBytes, xf_off);
-        wn4.load(wt, wf_off);
-#pragma unroll
-        for (int j = 0; j < kHalfRows; ++j) {
-            int c = (counts >> (4 * j)) & 15;         // uniform
-            while (c > 0) {
-                const frag4 xc = xn, wc = wn4;
-                xis = (int)((unsigned)xis >> 4);
-                wt += kTileBytes;
-                xn.load(wb + (xis & 15) * kTileBytes, xf_off);
-                wn4.load(wt, wf_off);
-                __builtin_amdgcn_sched_barrier(0);    // the reads are issued before the multiplications, not after them
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                    for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-                        for (int rt = 0; rt < 2; ++rt)
-                            acc[j][ct][rt] = mfma16<T>(wc.v[ct][ks], xc.v[rt][ks], acc[j][ct][rt]);
+        // this wavefront's row: its count, and the blocks of the rows before it (the window's blocks are sorted by row)
+        const int c = producer ? 0 : (int)((all_counts >> (4 * (wave & 7))) & 15u);
+        const unsigned below = all_counts & ((1u << (4 * (wave & 7))) - 1u);
+        const unsigned pairs = (below & 0x0f0f0f0fu) + ((below >> 4) & 0x0f0f0f0fu);
+        const int before = (int)((pairs * 0x01010101u) >> 24);
+        if (c > 0) {                                  // uniform
+            const unsigned char* wb = ring + w3 * (kWin * kTileBytes);
+            const unsigned char* wt = wb + (nx + before) * kTileBytes;       // the row's first block in this window
+            unsigned xsel = xis >> (4 * before);      // which X tile each of its blocks multiplies, 4 bits each
+            half_frag fa, fb;                         // k elements 0-31 and 32-63 of the block in turn
+            fa.load(wt, wb + (xsel & 15u) * kTileBytes, f_off);
+            fb.load(wt, wb + (xsel & 15u) * kTileBytes, f_off ^ 64u);
+            for (int i = 0; i < c; ++i) {
+                // behind the row's last block of the window the reads repeat that block's and are dropped
+                const bool more = i + 1 < c;
+                const unsigned char* wn = more ? wt + kTileBytes : wt;
+                const unsigned xnext = more ? xsel >> 4 : xsel;
+                const unsigned char* xn = wb + (xnext & 15u) * kTileBytes;
                 __builtin_amdgcn_sched_barrier(0);
-                --c;
+                multiply(fa);
+                __builtin_amdgcn_sched_barrier(0);
+                fa.load(wn, xn, f_off);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply(fb);
+                __builtin_amdgcn_sched_barrier(0);
+                fb.load(wn, xn, f_off ^ 64u);
+                __builtin_amdgcn_sched_barrier(0);
+                wt = wn;
+                xsel = xnext;
             }
         }
-        if (half == 1 && w + 2 < n_win) issue(rv, 32, w3 == 0 ? 2 : w3 - 1);
         w3 = w3 == 2 ? 0 : w3 + 1;
         rv = rv_next;
     }
@@ -285,18 +301,20 @@ __global__ __launch_bounds__(512) void bsr_mfma_group(const T* __restrict__ X, c
     // result of a 16x16 tile: lane l holds X row (l mod 16), 4 consecutive columns 4*(l div 16) ..
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     barrier();
+    {
+        // wavefront j holds row j's 64x64 result: tile (ct, rt) = columns 16ct.. of the block-row, rows 16rt.. of X
+        int my_row = -1;
 #pragma unroll
-    for (int jj = 0; jj < kHalfRows; ++jj) {
-        const int j = half * kHalfRows + jj;
-        if ((half == 0 ? rows[jj] : rows[kHalfRows + jj]) >= 0) {   // uniform; rows fill a group from the front
-            unsigned char* ob = ring + j * geo::OUT;
+        for (int j = 0; j < kG; ++j) my_row = wave == j ? rows[j] : my_row;
+        if (my_row >= 0) {                            // uniform
+            unsigned char* ob = ring + wave * geo::OUT;
 #pragma unroll
-            for (int ct = 0; ct < 2; ++ct)
+            for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-                for (int rt = 0; rt < 2; ++rt) {
-                    const int orow = 32 * wm + 16 * rt + fr, ocol = 32 * wn + 16 * ct + 4 * fq;
-                    store4<O>(reinterpret_cast<O*>(ob + orow * geo::OS) + ocol, acc[jj][ct][rt][0], acc[jj][ct][rt][1],
-                              acc[jj][ct][rt][2], acc[jj][ct][rt][3]);
+                for (int rt = 0; rt < 4; ++rt) {
+                    const int orow = 16 * rt + fr, ocol = 16 * ct + 4 * fq;
+                    store4<O>(reinterpret_cast<O*>(ob + orow * geo::OS) + ocol, acc[ct][rt][0], acc[ct][rt][1],
+                              acc[ct][rt][2], acc[ct][rt][3]);
                 }
         }
     }
@@ -304,7 +322,8 @@ __global__ __launch_bounds__(512) void bsr_mfma_group(const T* __restrict__ X, c
     barrier();
     const int i0 = sub * kSub;
     constexpr int PPR = geo::OB / 16;                 // 16-byte pieces per output row
-    constexpr int RPP = 512 / PPR;                    // rows per pass of the 512 threads
+    constexpr int RPP = 512 / PPR;                    // rows per pass of the first 512 threads (the moving wavefronts are done)
+    if (tid >= 512) return;
 #pragma unroll
     for (int j = 0; j < kG; ++j) {
         if (rows[j] >= 0) {
@@ -363,18 +382,9 @@ void build_group_plan(bsr_matrix* W, const int32_t* ptr, const int32_t* idx, siz
     }
     std::vector<int32_t> desc((size_t)n_groups * kDescWords, 0), recs;
     for (int q = 0; q < n_groups; ++q) {
-        // the group's rows 0-3 and 4-7 go to different wavefronts: deal the members (longest first) to the
-        // half with fewer blocks; positions without a row hold -1
+        // rows of the group longest first (the members were dealt out in that order): wavefront j takes row j
         std::vector<int32_t> rows(kG, -1);
-        {
-            int fill[2] = {0, 0};
-            int64_t blocks[2] = {0, 0};
-            for (int r : members[(size_t)q]) {
-                const int h = fill[0] >= kG / 2 ? 1 : fill[1] >= kG / 2 ? 0 : (blocks[1] < blocks[0] ? 1 : 0);
-                rows[(size_t)(h * (kG / 2) + fill[h]++)] = r;
-                blocks[h] += count(r);
-            }
-        }
+        for (size_t j = 0; j < members[(size_t)q].size(); ++j) rows[j] = members[(size_t)q][j];
         int32_t* d = desc.data() + (size_t)q * kDescWords;
         for (int j = 0; j < kG; ++j) d[j] = rows[(size_t)j];
         d[8] = (int32_t)(recs.size() / kRec);
@@ -449,7 +459,7 @@ bsr_status launch_group_types(const spmm_args& a)
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&bsr_mfma_group<T, O>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (attr != hipSuccess) return BSR_ERR_HIP;
-    hipLaunchKernelGGL((bsr_mfma_group<T, O>), dim3((unsigned)grid), dim3(512), kLdsBytes, a.stream, (const T*)a.X,
+    hipLaunchKernelGGL((bsr_mfma_group<T, O>), dim3((unsigned)grid), dim3(768), kLdsBytes, a.stream, (const T*)a.X,
                        (const T*)W->data, W->grp_recs, W->grp_desc, (O*)a.Y, m, k, n, W->grp_n, n_sub);
     return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
 }

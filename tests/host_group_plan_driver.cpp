@@ -2,7 +2,7 @@
 // patterns it builds the groups and their window records with the library's own host code and verifies what
 // the kernel relies on:
 //   - the grouped block-rows are exactly the leading grp_slots slots of the longest-first order, each in one
-//     group, at most 8 per group (4 per half); every one stores at least the minimum number of blocks;
+//     group, at most 8 per group, longest first; every one stores at least the minimum number of blocks;
 //   - every stored block of a grouped row appears exactly once in the records, counted under its own row of
 //     the group, pointing at an X tile of the same window whose block-column is the block's;
 //   - a window holds 2..6 tiles, X tiles first, then the stored blocks sorted by row of the group; its counts
@@ -73,14 +73,17 @@ int main()
         int next_rec = 0;
         for (int g = 0; g < W.grp_n; ++g) {
             const int32_t* d = desc + (size_t)g * 16;
-            int in_half[2] = {0, 0};
+            bool ended = false;
+            int prev_count = 1 << 30;
             for (int j = 0; j < 8; ++j) {
-                if (d[j] < 0) continue;
-                CHECK(d[j] < R && (j % 4 == 0 || d[j - 1] >= 0));   // each half of a group fills from its front
-                ++in_half[j / 4];
+                if (d[j] < 0) { ended = true; continue; }
+                CHECK(!ended && d[j] < R);                 // rows fill a group from the front, longest first
+                const int cnt = ptr[d[j] + 1] - ptr[d[j]];
+                CHECK(cnt <= prev_count);
+                prev_count = cnt;
                 ++row_seen[(size_t)d[j]];
             }
-            CHECK(in_half[0] >= 1 && in_half[0] <= 4 && in_half[1] <= 4);
+            CHECK(d[0] >= 0);
             CHECK(d[8] == next_rec && d[9] >= 1);
             next_rec += d[9];
             int prev = 0, prev2 = 0;
