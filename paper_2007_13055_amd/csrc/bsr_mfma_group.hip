@@ -60,7 +60,12 @@ constexpr int kG = 8;                                 // block-rows per group
 constexpr int kSub = 64;                              // rows of X per workgroup
 constexpr int kTileBytes = 8192;                      // a staged tile: 64 rows x 128 bytes
 constexpr int kSlots = 19;                            // ring slots: 3 windows of kWin, and one that is only ever read
-constexpr int kWin = 6;                               // tiles per window at most (3 windows fit the ring)
+#ifndef GRP_KWIN
+#define GRP_KWIN 6
+#define GRP_RING 3
+#endif
+constexpr int kWin = GRP_KWIN;                        // tiles per window at most
+constexpr int kRingWin = GRP_RING;                    // windows the ring holds: one in use, the others on their way
 constexpr int kRecLds = 128;                          // window records kept in LDS: two halves of 64, refilled in turn
 constexpr int kRec = 16;                              // words per window record
 constexpr int kRecTilesAt = 4;
@@ -69,7 +74,7 @@ constexpr int kRecBytes = kRecLds * kRec * 4;         // 8 KiB
 constexpr int kLdsBytes = kRecBytes + kSlots * kTileBytes;
 constexpr int kHeavyMin = 8;                          // a grouped block-row stores at least this many blocks
 constexpr int kMaxGroups = 2;
-static_assert(3 * kWin + 1 <= kSlots, "three windows and the slot behind them");
+static_assert(kRingWin * kWin <= kSlots && (kRingWin == 2 || kRingWin == 3) && kWin <= 9, "the windows fit the ring; a record lists at most 9 tiles");
 
 template <int N>
 __device__ __forceinline__ void wait_vm()
@@ -241,13 +246,13 @@ __global__ __launch_bounds__(768) void bsr_mfma_group(const T* __restrict__ X, c
     int rv = read_records(0);
     if (producer) {
         issue(rv, 0, 0);
-        if (n_win > 1) issue(rv, 16, 1);
+        if (kRingWin == 3 && n_win > 1) issue(rv, 16, 1);
     }
 
     int w3 = 0;                                       // w mod 3
     for (int w = 0; w < n_win; ++w) {
         if (producer) {
-            const int next_tiles = w + 1 < n_win ? (__builtin_amdgcn_readlane(rv, 17) & 15) : 0;
+            const int next_tiles = kRingWin == 3 && w + 1 < n_win ? (__builtin_amdgcn_readlane(rv, 17) & 15) : 0;
             wait_all_but_tiles(next_tiles);           // this wavefront's share of window w has landed
         }
         barrier();                                    // ... everybody's has, and everybody is done with window w-1
@@ -256,7 +261,8 @@ __global__ __launch_bounds__(768) void bsr_mfma_group(const T* __restrict__ X, c
             // every 64 windows the half of the record area that was used up takes the records 64 .. 127 ahead
             // (loads complete in order, so they have landed, for everybody, many windows before they are read)
             if ((w & 63) == 0 && w > 0 && w + 64 < n_win) load_records((w >> 6) + 1);
-            if (w + 2 < n_win) issue(rv, 32, w3 == 0 ? 2 : w3 - 1);   // window w+2 takes the slots of window w-1
+            // the window kRingWin - 1 ahead takes the slots of window w-1
+            if (w + kRingWin - 1 < n_win) issue(rv, 16 * (kRingWin - 1), w3 == 0 ? kRingWin - 1 : w3 - 1);
         }
         const unsigned all_counts = (unsigned)__builtin_amdgcn_readlane(rv, 0);
         const int info = __builtin_amdgcn_readlane(rv, 1);
@@ -271,29 +277,39 @@ __global__ __launch_bounds__(768) void bsr_mfma_group(const T* __restrict__ X, c
             const unsigned char* wb = ring + w3 * (kWin * kTileBytes);
             const unsigned char* wt = wb + (nx + before) * kTileBytes;       // the row's first block in this window
             unsigned xsel = xis >> (4 * before);      // which X tile each of its blocks multiplies, 4 bits each
-            half_frag fa, fb;                         // k elements 0-31 and 32-63 of the block in turn
+            // fa / fb: k elements 0-31 / 32-63 of the block in turn.  While one half is multiplied the other
+            // half's operands are read: 8 LDS reads interleaved with the first 8 of the 16 MFMAs.
+            half_frag fa, fb;
             fa.load(wt, wb + (xsel & 15u) * kTileBytes, f_off);
-            fb.load(wt, wb + (xsel & 15u) * kTileBytes, f_off ^ 64u);
             for (int i = 0; i < c; ++i) {
                 // behind the row's last block of the window the reads repeat that block's and are dropped
                 const bool more = i + 1 < c;
                 const unsigned char* wn = more ? wt + kTileBytes : wt;
                 const unsigned xnext = more ? xsel >> 4 : xsel;
-                const unsigned char* xn = wb + (xnext & 15u) * kTileBytes;
                 __builtin_amdgcn_sched_barrier(0);
+                fb.load(wt, wb + (xsel & 15u) * kTileBytes, f_off ^ 64u);
                 multiply(fa);
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
                 __builtin_amdgcn_sched_barrier(0);
-                fa.load(wn, xn, f_off);
-                __builtin_amdgcn_sched_barrier(0);
+                fa.load(wn, wb + (xnext & 15u) * kTileBytes, f_off);
                 multiply(fb);
-                __builtin_amdgcn_sched_barrier(0);
-                fb.load(wn, xn, f_off ^ 64u);
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 wt = wn;
                 xsel = xnext;
             }
         }
-        w3 = w3 == 2 ? 0 : w3 + 1;
+        w3 = w3 == kRingWin - 1 ? 0 : w3 + 1;
         rv = rv_next;
     }
 
