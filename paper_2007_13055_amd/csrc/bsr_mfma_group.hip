@@ -12,40 +12,45 @@
 //
 // Plan (bsr_create).  The grouped rows are the leading slots of the longest-first order that store
 // at least kHeavyMin blocks, at most 8 per group and kMaxGroups groups, dealt out so that the groups
-// hold about equal numbers of blocks.  A group's work is a stream of 8 KiB tiles -- the X tile of a
-// block-column, then the stored blocks of that column -- cut into WINDOWS of at most kWin tiles:
-// whole columns, except that a column with more blocks than fit is continued in the next window
-// with its X tile staged again.  One 16-word record per window:
+// hold about equal numbers of blocks; inside a group the rows come longest first.  A group's work is a
+// stream of 8 KiB tiles -- the X tile of a block-column, then the stored blocks of that column -- cut
+// into WINDOWS of at most kWin tiles: whole columns, except that a column with more blocks than fit is
+// continued in the next window with its X tile staged again.  One 16-word record per window:
 //   word 0   stored blocks per row of the group in this window, 4 bits each (row j at bits 4j..4j+3)
 //   word 1   tiles in the window (bits 0-3), X tiles among them (bits 4-7)
 //   word 2   for the window's i-th stored block, 4 bits each: which of the window's X tiles it multiplies
 //   word 4.. the tiles: first the X tiles (0x80000000 | block-column), then the stored blocks
 //            (stored-block number) sorted by row of the group
 //
+// Workgroup: 12 wavefronts, three per SIMD.  Wavefront j < 8 multiplies the group's row j; wavefronts
+// 8-11 only move tiles.  (A wavefront that issues loads waits for the memory pipeline to take them,
+// about 130 cycles per 1 KiB load while a window streams in; one that multiplied as well would be the
+// last at every barrier.)
+//
 // Data movement.  Tiles go from global memory straight into LDS (global_load_lds_dwordx4: no staging
 // registers).  The ring holds three windows of kWin slots, window w in the slots (w mod 3) * kWin ..;
-// every wavefront moves an eighth (8 rows) of every tile, so all wavefronts issue the same number of
-// loads per tile.  Loads complete in issue order: before window w is multiplied a wavefront waits
-// until only its loads of window w+1 are outstanding, then the workgroup meets at a barrier -- which
-// also says that everybody is done with window w-1 -- and the loads of window w+2 are issued into the
-// slots of window w-1.  A 16-byte piece q of row i of a tile lies at piece position q ^ (i mod 8) of
-// its 128-byte LDS row, which makes the operand reads of 16 consecutive rows at one k offset
-// conflict-free without padding.  The window records travel the same way, 64 at a time, into an 8 KiB
-// record area in front of the ring, and are read from there one word per lane (scalar loads from
-// global memory cost a cache miss per window on the critical path).
+// each of the four moving wavefronts takes a quarter (16 rows) of every tile.  Loads complete in issue
+// order: before window w is multiplied a moving wavefront waits until only its loads of window w+1 are
+// outstanding, then the workgroup meets at a barrier -- which also says that everybody is done with
+// window w-1 -- and the loads of window w+2 are issued into the slots of window w-1.  A 16-byte piece
+// q of row i of a tile lies at piece position q ^ (i mod 8) of its 128-byte LDS row, which makes the
+// operand reads of 16 consecutive rows at one k offset conflict-free without padding.  The window
+// records travel the same way, 64 at a time, into an 8 KiB record area in front of the ring, and are
+// read from there one word per lane (scalar loads from global memory cost a cache miss per window on
+// the critical path).
 //
-// Arithmetic.  8 wavefronts, two per SIMD: wavefronts 0-3 take the group's rows 0-3, wavefronts 4-7 its
-// rows 4-7 (the plan balances the two halves), each a quadrant (32 rows of X x 32 rows of the block) of
-// every block product of its rows: v_mfma_f32_16x16x32 on 2x2 tiles, 4 independent accumulators per
-// block-row, 64 accumulator registers per lane.  Inside a window the stored blocks are taken row of the
-// group by row of the group, so the accumulator a block adds to is known at compile time; the operands
-// of the next block are read from LDS while the current one is multiplied.
+// Arithmetic.  A wavefront multiplies whole 64x64 blocks of its row: v_mfma_f32_16x16x32 on 4x4 tiles, 16
+// independent accumulators (64 registers per lane), the accumulator a block adds to known at compile
+// time.  It holds the operands of one k half of a block at a time (4 tiles of the block, 4 of X) in each
+// of two register sets; while one half is multiplied (16 MFMAs) the eight LDS reads of the half after
+// the next are interleaved with the first eight of them.  Every stored block costs 16 KiB of LDS reads
+// (quadrants shared by four wavefronts cost 32 KiB and twice the instructions per flop).
 //
-// Measured on the 8192^3 power-law workload (16 grouped rows = 573 of 819 blocks): the group kernel
-// fetches 196 MB from beyond L2 where the tile kernel fetches 522 MB for the same rows, but takes
-// 105 us against 107 us: a workgroup streams 3.3 MB of tiles per 64 rows of X and one CU takes in
-// 35-40 bytes per clock at best, and the LDS writes of the arriving tiles and the operand reads share
-// the LDS.  It is therefore not the default (BSR_SPMM_TUNE variant=5 selects it).
+// Measured on the 8192^3 power-law workload (16 grouped rows = 573 of 819 blocks): this kernel fetches
+// 221 MB from beyond L2 where the tile kernel fetches 601 MB for the same rows, and takes about 65 us
+// for them against 105 us; with the tile kernel for the other rows the product takes 117 us instead of
+// 135 us and fetches 405 instead of 825 MB.  What bounds it: a workgroup streams 3.3 MB of tiles per 64
+// rows of X, and a CU takes in about 30 bytes per clock while its LDS also serves the operand reads.
 #include <algorithm>
 #include <numeric>
 
