@@ -630,6 +630,7 @@ static std::vector<tuned_choice> tune_candidates(const bsr_matrix* W, int64_t m)
             for (int nw : {2, 4, 8})
                 for (int per : {1, 2, 4}) add(BSR_PATH_MFMA, 2, nw, mt, per, 0);
         }
+        if (mfma_group_supports(W) && m >= 64) add(BSR_PATH_MFMA, 5, 0, 0, 0, 0);   // long rows in row groups + tile kernel
         if (W->bs_r >= 32 && m >= 128) {
             for (int depth : {2, 3, 4}) add(BSR_PATH_MFMA, 3, 0, 1, depth, 0);
             for (int depth : {1, 2}) add(BSR_PATH_MFMA, 3, 0, 2, depth, 0);

@@ -195,6 +195,7 @@ bsr_status launch_mfma(const spmm_args& a, const tune_opts& tune)
         // the grouped (longest) block-rows in one launch, the other slots through the tile kernel
         if (!mfma_group_supports(a.W)) return launch_mfma_tile(a, t);   // no block-row long enough
         const bsr_status st = launch_mfma_group(a, t);
+        if (st == BSR_ERR_UNSUPPORTED) return launch_mfma_tile(a, t);   // sizes beyond its 32-bit offsets: nothing was launched
         if (st != BSR_OK) return st;
         spmm_args rest = a;
         rest.first_slot = a.W->grp_slots;
