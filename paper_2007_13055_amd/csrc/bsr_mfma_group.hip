@@ -12,32 +12,40 @@
 //
 // Plan (bsr_create).  The grouped rows are the leading slots of the longest-first order that store
 // at least kHeavyMin blocks, at most 8 per group and kMaxGroups groups, dealt out so that the groups
-// hold about equal numbers of blocks; inside a group the rows come longest first.  A group's work is a
-// stream of 8 KiB tiles -- the X tile of a block-column, then the stored blocks of that column -- cut
-// into WINDOWS of at most kWin tiles: whole columns, except that a column with more blocks than fit is
-// continued in the next window with its X tile staged again.  One 16-word record per window:
-//   word 0   stored blocks per row of the group in this window, 4 bits each (row j at bits 4j..4j+3)
+// hold about equal numbers of blocks.  A group has 8 multiplying wavefronts: each row gets one, and
+// wavefronts that are left over go to the rows with the most blocks per wavefront, which are cut into
+// SHARES (the row's blocks in column order, dealt round); the order of the rows over the wavefronts is
+// the one that leaves the busiest SIMD the fewest blocks.  A group's work is a stream of 8 KiB tiles --
+// the X tile of a block-column, then the stored blocks of that column -- cut into WINDOWS of at most
+// kWin tiles: whole columns (a column with more blocks than fit is cut, each part with the X tile),
+// starting with the first column not yet placed and filled up with the best-fitting of the next
+// kLookAhead ones, so that nearly every window is full and the groups still pass over the
+// block-columns at about the same time.  One 16-word record per window:
+//   word 0   stored blocks per wavefront of the group in this window, 4 bits each (wavefront j at bits 4j..4j+3)
 //   word 1   tiles in the window (bits 0-3), X tiles among them (bits 4-7)
 //   word 2   for the window's i-th stored block, 4 bits each: which of the window's X tiles it multiplies
-//   word 4.. the tiles: first the X tiles (0x80000000 | block-column), then the stored blocks
-//            (stored-block number) sorted by row of the group
+//   word 4.. the tiles by byte offset: first the X tiles (block-column * 128, into a row of X), then the
+//            stored blocks (stored-block number * 8192, into block_data) sorted by wavefront
+// Group descriptor (16 words): the block-row of each of the 8 wavefronts (-1: none; the wavefronts of
+// a row follow each other), the group's first record, its number of windows.
 //
-// Workgroup: 12 wavefronts, three per SIMD.  Wavefront j < 8 multiplies the group's row j; wavefronts
-// 8-11 only move tiles.  (A wavefront that issues loads waits for the memory pipeline to take them,
-// about 130 cycles per 1 KiB load while a window streams in; one that multiplied as well would be the
-// last at every barrier.)
+// Workgroup: 12 wavefronts, three per SIMD.  Wavefront j < 8 multiplies the blocks counted for it;
+// wavefronts 8-11 only move tiles.  (A wavefront that issues loads waits for the memory pipeline to
+// take them, about 130 cycles per 1 KiB load while a window streams in; one that multiplied as well
+// would be the last at every barrier.)
 //
 // Data movement.  Tiles go from global memory straight into LDS (global_load_lds_dwordx4: no staging
 // registers).  The ring holds three windows of kWin slots, window w in the slots (w mod 3) * kWin ..;
-// each of the four moving wavefronts takes a quarter (16 rows) of every tile.  Loads complete in issue
-// order: before window w is multiplied a moving wavefront waits until only its loads of window w+1 are
-// outstanding, then the workgroup meets at a barrier -- which also says that everybody is done with
-// window w-1 -- and the loads of window w+2 are issued into the slots of window w-1.  A 16-byte piece
-// q of row i of a tile lies at piece position q ^ (i mod 8) of its 128-byte LDS row, which makes the
-// operand reads of 16 consecutive rows at one k offset conflict-free without padding.  The window
-// records travel the same way, 64 at a time, into an 8 KiB record area in front of the ring, and are
-// read from there one word per lane (scalar loads from global memory cost a cache miss per window on
-// the critical path).
+// each of the four moving wavefronts takes a quarter (16 rows, two 1 KiB loads) of every tile (built with
+// GRP_G = 6: six wavefronts multiply, six move tiles, each one half of every third tile).  Loads
+// complete in issue order: before window w is multiplied a moving wavefront waits until only its loads
+// of window w+1 are outstanding, then the workgroup meets at a barrier -- which also says that
+// everybody is done with window w-1 -- and the loads of window w+2 are issued into the slots of window
+// w-1.  A 16-byte piece q of row i of a tile lies at piece position q ^ (i mod 8) of its 128-byte LDS
+// row, which makes the operand reads of 16 consecutive rows at one k offset conflict-free without
+// padding.  The window records travel the same way, 64 at a time, into an 8 KiB record area in front
+// of the ring, and are read from there one word per lane (scalar loads from global memory cost a cache
+// miss per window on the critical path).
 //
 // Arithmetic.  A wavefront multiplies whole 64x64 blocks of its row: v_mfma_f32_16x16x32 on 4x4 tiles, 16
 // independent accumulators (64 registers per lane), the accumulator a block adds to known at compile
@@ -46,11 +54,16 @@
 // the next are interleaved with the first eight of them.  Every stored block costs 16 KiB of LDS reads
 // (quadrants shared by four wavefronts cost 32 KiB and twice the instructions per flop).
 //
-// Measured on the 8192^3 power-law workload (16 grouped rows = 573 of 819 blocks): this kernel fetches
-// 221 MB from beyond L2 where the tile kernel fetches 601 MB for the same rows, and takes about 65 us
-// for them against 105 us; with the tile kernel for the other rows the product takes 117 us instead of
-// 135 us and fetches 405 instead of 825 MB.  What bounds it: a workgroup streams 3.3 MB of tiles per 64
-// rows of X, and a CU takes in about 30 bytes per clock while its LDS also serves the operand reads.
+// Results.  Every multiplying wavefront writes its 64x64 fp32 result into LDS; the shares of a row are
+// added there in wavefront order, rounded once to the type of Y, and whole rows are stored.
+//
+// Measured on the 8192^3 power-law workload (16 grouped rows = 573 of 819 blocks, 75 and 73 windows):
+// this kernel fetches about 220 MB from beyond L2 where the tile kernel fetches 601 MB for the same
+// rows, and takes about 65 us for them against 105 us; with the tile kernel for the other rows the
+// product takes 113-116 us instead of 135 us.  What bounds it: a workgroup streams 3.3 MB of tiles
+// per 64 rows of X; with the multiplying switched off the kernel takes 50 us (a CU takes in about
+// 30 bytes per clock), with the loads switched off 51-55 us (per window the busiest SIMD multiplies
+// two blocks while the average is one), and the two overlap only partly behind one barrier per window.
 #include <algorithm>
 #include <numeric>
 
@@ -61,7 +74,15 @@ using namespace bsr_dev;
 namespace {
 
 constexpr int kXcds = 8;
-constexpr int kG = 8;                                 // block-rows per group
+#ifndef GRP_G
+#define GRP_G 8
+#endif
+constexpr int kG = GRP_G;                             // block-rows per group: wavefronts that multiply
+constexpr int kLoaders = 12 - kG;                     // wavefronts that only move tiles
+constexpr int kSplit = kLoaders == 6 ? 2 : 4;         // a tile moves as kSplit units of 8 / kSplit loads (1 KiB, 8 rows each)
+constexpr int kLpu = 8 / kSplit;                      // loads per unit
+constexpr int kTileStep = kLoaders / kSplit;          // a moving wavefront takes every kTileStep-th tile of a window
+static_assert(kG >= 1 && kG <= 8 && kLoaders >= 4 && kLoaders % kSplit == 0 && (kLpu == 2 || kLpu == 4), "a record counts 8 rows; four wavefronts move the records");
 constexpr int kSub = 64;                              // rows of X per workgroup
 constexpr int kTileBytes = 8192;                      // a staged tile: 64 rows x 128 bytes
 constexpr int kSlots = 19;                            // ring slots: 3 windows of kWin, and one that is only ever read
@@ -79,6 +100,10 @@ constexpr int kRecBytes = kRecLds * kRec * 4;         // 8 KiB
 constexpr int kLdsBytes = kRecBytes + kSlots * kTileBytes;
 constexpr int kHeavyMin = 8;                          // a grouped block-row stores at least this many blocks
 constexpr int kMaxGroups = 2;
+#ifndef GRP_LOOK
+#define GRP_LOOK 8
+#endif
+constexpr int kLookAhead = GRP_LOOK;                  // how far behind a window's first block-column the plan looks for more to fill it
 static_assert(kRingWin * kWin <= kSlots && (kRingWin == 2 || kRingWin == 3) && kWin <= 9, "the windows fit the ring; a record lists at most 9 tiles");
 
 template <int N>
@@ -87,16 +112,22 @@ __device__ __forceinline__ void wait_vm()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// Returns when at most the loads of `tiles` tiles (two per tile and moving wavefront, the youngest) are still in flight.
-__device__ __forceinline__ void wait_all_but_tiles(int tiles)
+// Returns when at most the `loads` youngest loads of this wavefront are still in flight.
+__device__ __forceinline__ void wait_all_but(int loads)
 {
-    switch (tiles) {
+    switch (loads) {
         case 0: wait_vm<0>(); break;
-        case 1: wait_vm<2>(); break;
-        case 2: wait_vm<4>(); break;
-        case 3: wait_vm<6>(); break;
-        case 4: wait_vm<8>(); break;
-        case 5: wait_vm<10>(); break;
+        case 1: wait_vm<1>(); break;
+        case 2: wait_vm<2>(); break;
+        case 3: wait_vm<3>(); break;
+        case 4: wait_vm<4>(); break;
+        case 5: wait_vm<5>(); break;
+        case 6: wait_vm<6>(); break;
+        case 7: wait_vm<7>(); break;
+        case 8: wait_vm<8>(); break;
+        case 9: wait_vm<9>(); break;
+        case 10: wait_vm<10>(); break;
+        case 11: wait_vm<11>(); break;
         default: wait_vm<12>(); break;
     }
 }
@@ -125,13 +156,10 @@ struct frag4 {
     }
 };
 
-template <typename O>
-struct out_geom {
-    static constexpr int OB = 64 * (int)sizeof(O);    // bytes of one output row of a block-row
-    static constexpr int OS = OB + 16;                // padded LDS stride
-    static constexpr int OUT = 64 * OS;               // one block-row's staging buffer
-    static_assert(kG * OUT <= kSlots * kTileBytes, "the group's results fit the ring");
-};
+// Results leave a wavefront as fp32 through LDS: one 64x64 staging buffer per multiplying wavefront.
+constexpr int kStageStride = 64 * 4 + 16;             // bytes of a staged row, padded
+constexpr int kStage = 64 * kStageStride;
+static_assert(kG * kStage <= kSlots * kTileBytes, "the group's results fit the ring");
 
 template <typename T, typename O>
 __global__ __launch_bounds__(768) void bsr_mfma_group(const T* __restrict__ X, const T* __restrict__ data,
@@ -139,20 +167,19 @@ __global__ __launch_bounds__(768) void bsr_mfma_group(const T* __restrict__ X, c
                                                       const int32_t* __restrict__ gdesc, O* __restrict__ Y,
                                                       int m, int k, int n, int n_groups, int n_sub)
 {
-    typedef out_geom<O> geo;
     typedef __attribute__((address_space(3))) void lds_void;
     typedef __attribute__((address_space(1))) const void glob_void;
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     unsigned char* const ring = lds + kRecBytes;      // records first, then the ring of tiles
 
-    // 12 wavefronts, three per SIMD.  Wavefront j < 8 multiplies the group's row j (the rows come longest
-    // first); wavefronts 8-11 only move tiles, each a quarter (16 rows) of every tile: a wavefront that
-    // issues loads waits for the memory pipeline to take them (about 100 cycles per 1 KiB load while a
-    // window streams in), and a wavefront that multiplied as well would be the last at every barrier.
+    // 12 wavefronts, three per SIMD.  Wavefront j < kG multiplies the blocks the records count for it (a
+    // block-row of the group, or a share of one); the others only move tiles: a wavefront that issues
+    // loads waits for the memory pipeline to take them (about 130 cycles per 1 KiB load while a window
+    // streams in), and a wavefront that multiplied as well would be the last at every barrier.
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool producer = wave >= kG;
-    const int pq = wave & 3;
+    const int pq = wave - kG;                         // which of the moving wavefronts (negative: none)
 
     // workgroup -> (64-row sub-tile of X, group): XCD x (which receives the workgroups b = x mod 8) takes the
     // sub-tiles x, x+8, ..., and the groups of a sub-tile follow each other on that XCD, so the second
@@ -161,41 +188,54 @@ __global__ __launch_bounds__(768) void bsr_mfma_group(const T* __restrict__ X, c
     const int sub = (local / n_groups) * kXcds + xcd, g = local % n_groups;
     if (sub >= n_sub) return;                         // whole workgroup: the grid is padded to whole rounds of XCDs
     const int32_t* __restrict__ gd = gdesc + (size_t)g * kDescWords;   // uniform
-    int rows[kG];
-#pragma unroll
-    for (int j = 0; j < kG; ++j) rows[j] = gd[j];
     const int n_win = gd[9];
+    if (n_win <= 0) return;                           // whole workgroup (a plan has no such group)
     const int32_t* __restrict__ rec = recs + (size_t)gd[8] * kRec;
 
-    // ---- moving tiles: wavefront 4+q takes rows 16q .. 16q+15 of every tile, two 1 KiB loads ----
-    // load i covers rows 16q + 8i .. +7: lane l moves the 16 bytes at piece position l mod 8 of row
-    // 16q + 8i + l div 8, which hold the row's piece (position ^ row mod 8)
+    // ---- moving tiles: 1 KiB loads, each 8 rows of a tile ----
+    // lane l moves the 16 bytes at piece position l mod 8 of the load's row l div 8, which hold the row's
+    // piece (position ^ row mod 8)
     const unsigned char* Xb = reinterpret_cast<const unsigned char*>(X);
     const unsigned char* Wb = reinterpret_cast<const unsigned char*>(data);
     const int lrow = lane >> 3;
     const unsigned piece = (unsigned)((lane & 7) ^ lrow) * 16u;
     const unsigned row_bytes = (unsigned)k * (unsigned)sizeof(T);
-    // byte offsets of the lane's two pieces (m*k*2 < 2^32); rows past m repeat row m-1, their results are never stored
-    const int prow0 = 16 * pq + lrow, prow1 = prow0 + 8;
-    const unsigned x_off0 = (unsigned)min(sub * kSub + prow0, m - 1) * row_bytes + piece;
-    const unsigned x_off1 = (unsigned)min(sub * kSub + prow1, m - 1) * row_bytes + piece;
-    const unsigned w_off0 = (unsigned)prow0 * 128u + piece, w_off1 = (unsigned)prow1 * 128u + piece;
+    // Moving wavefront q takes the same part (q mod kSplit: 64 / kSplit rows) of the tiles q div kSplit,
+    // q div kSplit + kTileStep, ... of every window: kLpu loads each.  A record names a tile by its byte
+    // offset: block-column * 128 into a row of X, stored block * 8192 into the blocks; the window's first nx
+    // tiles are X tiles.  Byte offsets into X fit 32 bits (m*k*2 < 2^32); rows past m repeat row m-1, their
+    // results are never stored.
+    const int part = pq & (kSplit - 1), t0 = pq / kSplit;
+    const unsigned char* xa[kLpu];                    // the lane's address in block-column 0 of X, per load
+#pragma unroll
+    for (int i = 0; i < kLpu; ++i)
+        xa[i] = Xb + ((unsigned)min(sub * kSub + part * (kSub / kSplit) + 8 * i + lrow, m - 1) * row_bytes + piece);
+    const unsigned char* const wa = Wb + ((unsigned)(part * (kSub / kSplit) + lrow) * 128u + piece);
+    auto loads_of = [&](int nt) { return nt > t0 ? kLpu * ((nt - t0 + kTileStep - 1) / kTileStep) : 0; };
     // Window w lives in the kWin slots starting at slot (w mod 3) * kWin, tile i in the i-th of them.
     // A window's record is read from LDS one word per lane (rv: lanes 16q .. 16q+15 hold record w+q) and
     // its words are taken out with lane reads; `at` = lane of the record's word 0.
     auto issue = [&](int rv, int at, int w3) __attribute__((always_inline)) {   // the tiles of one window
-        const int nt = __builtin_amdgcn_readlane(rv, at + 1) & 15;
-        unsigned char* dst = ring + w3 * (kWin * kTileBytes) + pq * 2048;
-        for (int i = 0; i < nt; ++i, dst += kTileBytes) {
-            const int code = __builtin_amdgcn_readlane(rv, at + kRecTilesAt + i);
-            if (code < 0) {                           // X tile of a block-column
-                const unsigned char* base = Xb + (size_t)(code & 0x7fffffff) * 128u;
-                __builtin_amdgcn_global_load_lds((glob_void*)(base + x_off0), (lds_void*)dst, 16, 0, 0);
-                __builtin_amdgcn_global_load_lds((glob_void*)(base + x_off1), (lds_void*)(dst + 1024), 16, 0, 0);
-            } else {                                  // a stored block
-                const unsigned char* base = Wb + (size_t)code * (size_t)kTileBytes;
-                __builtin_amdgcn_global_load_lds((glob_void*)(base + w_off0), (lds_void*)dst, 16, 0, 0);
-                __builtin_amdgcn_global_load_lds((glob_void*)(base + w_off1), (lds_void*)(dst + 1024), 16, 0, 0);
+        const int info = __builtin_amdgcn_readlane(rv, at + 1);
+        const int nt = info & 15, nx = (info >> 4) & 15;
+        unsigned char* dst = ring + w3 * (kWin * kTileBytes) + t0 * kTileBytes + part * (kTileBytes / kSplit);
+#pragma unroll
+        for (int j = 0; j < (kWin + kTileStep - 1) / kTileStep; ++j, dst += kTileStep * kTileBytes) {
+            const int t = t0 + j * kTileStep;
+            if (t >= nt) break;
+            const unsigned code = (unsigned)__builtin_amdgcn_readlane(rv, at + kRecTilesAt + t);
+            if (t < nx) {                             // X tile of a block-column: the rows are k elements apart
+#pragma unroll
+                for (int i = 0; i < kLpu; ++i)
+                    __builtin_amdgcn_global_load_lds((glob_void*)(xa[i] + code), (lds_void*)(dst + i * 1024), 16, 0, 0);
+            } else {                                  // a stored block: 8 KiB in one piece
+                const unsigned char* src = wa + code;
+                __builtin_amdgcn_global_load_lds((glob_void*)src, (lds_void*)dst, 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((glob_void*)src, (lds_void*)dst, 16, 1024, 0);
+                if constexpr (kLpu == 4) {
+                    __builtin_amdgcn_global_load_lds((glob_void*)src, (lds_void*)dst, 16, 2048, 0);
+                    __builtin_amdgcn_global_load_lds((glob_void*)src, (lds_void*)dst, 16, 3072, 0);
+                }
             }
         }
     };
@@ -203,6 +243,7 @@ __global__ __launch_bounds__(768) void bsr_mfma_group(const T* __restrict__ X, c
     // group's last record repeat its last piece (never used)
     const int last_piece = n_win * (kRec / 4) - 1;
     auto load_records = [&](int chunk) __attribute__((always_inline)) {
+        if (pq >= 4) return;
         const int pc = min(chunk * 256 + pq * 64 + lane, last_piece);
         __builtin_amdgcn_global_load_lds((glob_void*)(reinterpret_cast<const unsigned char*>(rec) + (size_t)pc * 16),
                                          (lds_void*)(lds + (chunk & 1) * (kRecBytes / 2) + pq * 1024), 16, 0, 0);
@@ -258,7 +299,7 @@ __global__ __launch_bounds__(768) void bsr_mfma_group(const T* __restrict__ X, c
     for (int w = 0; w < n_win; ++w) {
         if (producer) {
             const int next_tiles = kRingWin == 3 && w + 1 < n_win ? (__builtin_amdgcn_readlane(rv, 17) & 15) : 0;
-            wait_all_but_tiles(next_tiles);           // this wavefront's share of window w has landed
+            wait_all_but(loads_of(next_tiles));       // this wavefront's share of window w has landed
         }
         barrier();                                    // ... everybody's has, and everybody is done with window w-1
         const int rv_next = read_records(w + 1);      // used in the next trip
@@ -273,7 +314,7 @@ __global__ __launch_bounds__(768) void bsr_mfma_group(const T* __restrict__ X, c
         const int info = __builtin_amdgcn_readlane(rv, 1);
         const unsigned xis = (unsigned)__builtin_amdgcn_readlane(rv, 2);
         const int nx = (info >> 4) & 15;
-        // this wavefront's row: its count, and the blocks of the rows before it (the window's blocks are sorted by row)
+        // this wavefront's blocks: how many, and how many belong to the wavefronts before it (the window's blocks are sorted by wavefront)
         const int c = producer ? 0 : (int)((all_counts >> (4 * (wave & 7))) & 15u);
         const unsigned below = all_counts & ((1u << (4 * (wave & 7))) - 1u);
         const unsigned pairs = (below & 0x0f0f0f0fu) + ((below >> 4) & 0x0f0f0f0fu);
@@ -318,46 +359,63 @@ __global__ __launch_bounds__(768) void bsr_mfma_group(const T* __restrict__ X, c
         rv = rv_next;
     }
 
-    // ---- epilogue: the group's block-rows through LDS (the ring is free: no load is outstanding), whole rows to Y ----
+    // ---- epilogue: every wavefront's 64x64 fp32 result through LDS (the ring is free: no load is outstanding);
+    // a block-row is the sum of its wavefronts' results, in wavefront order, then whole rows go to Y ----
     // result of a 16x16 tile: lane l holds X row (l mod 16), 4 consecutive columns 4*(l div 16) ..
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     barrier();
-    {
-        // wavefront j holds row j's 64x64 result: tile (ct, rt) = columns 16ct.. of the block-row, rows 16rt.. of X
-        int my_row = -1;
+    if (!producer && gd[wave] >= 0) {                 // uniform
+        unsigned char* ob = ring + wave * kStage;
 #pragma unroll
-        for (int j = 0; j < kG; ++j) my_row = wave == j ? rows[j] : my_row;
-        if (my_row >= 0) {                            // uniform
-            unsigned char* ob = ring + wave * geo::OUT;
+        for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-            for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-                for (int rt = 0; rt < 4; ++rt) {
-                    const int orow = 16 * rt + fr, ocol = 16 * ct + 4 * fq;
-                    store4<O>(reinterpret_cast<O*>(ob + orow * geo::OS) + ocol, acc[ct][rt][0], acc[ct][rt][1],
-                              acc[ct][rt][2], acc[ct][rt][3]);
-                }
-        }
+            for (int rt = 0; rt < 4; ++rt)
+                *reinterpret_cast<f32x4*>(ob + (16 * rt + fr) * kStageStride + (16 * ct + 4 * fq) * 4) = acc[ct][rt];
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     barrier();
     const int i0 = sub * kSub;
-    constexpr int PPR = geo::OB / 16;                 // 16-byte pieces per output row
-    constexpr int RPP = 512 / PPR;                    // rows per pass of the first 512 threads (the moving wavefronts are done)
+    constexpr int EPP = 16 / (int)sizeof(O);          // elements of Y per 16-byte piece
+    constexpr int PPR = 64 / EPP;                     // pieces per output row of a block-row
+    constexpr int RPP = 512 / PPR;                    // rows per pass of the first 512 threads
     if (tid >= 512) return;
-#pragma unroll
-    for (int j = 0; j < kG; ++j) {
-        if (rows[j] >= 0) {
-            const unsigned char* ob = ring + j * geo::OUT;
-            unsigned char* yb = reinterpret_cast<unsigned char*>(Y + (size_t)rows[j] * 64);
+    for (int j = 0; j < kG;) {                        // uniform: the wavefronts of a block-row follow each other
+        const int r = gd[j];
+        int shares = 1;
+        while (j + shares < kG && gd[j + shares] == r) ++shares;
+        if (r >= 0) {
+            unsigned char* yb = reinterpret_cast<unsigned char*>(Y + (size_t)r * 64);
 #pragma unroll
             for (int pass = 0; pass < 64 / RPP; ++pass) {
                 const int row = pass * RPP + tid / PPR, pc = tid % PPR;
-                const u32x4 v = *reinterpret_cast<const u32x4*>(ob + row * geo::OS + pc * 16);
+                const unsigned char* src = ring + j * kStage + row * kStageStride + pc * (EPP * 4);
+                float v[EPP];
+#pragma unroll
+                for (int e = 0; e < EPP; e += 4) {
+                    const f32x4 t = *reinterpret_cast<const f32x4*>(src + e * 4);
+                    v[e] = t[0]; v[e + 1] = t[1]; v[e + 2] = t[2]; v[e + 3] = t[3];
+                }
+                for (int sh = 1; sh < shares; ++sh) {
+#pragma unroll
+                    for (int e = 0; e < EPP; e += 4) {
+                        const f32x4 t = *reinterpret_cast<const f32x4*>(src + sh * kStage + e * 4);
+                        v[e] += t[0]; v[e + 1] += t[1]; v[e + 2] += t[2]; v[e + 3] += t[3];
+                    }
+                }
+                u32x4 out;
+                if constexpr (std::is_same<O, float>::value) {
+                    out = __builtin_bit_cast(u32x4, f32x4{v[0], v[1], v[2], v[3]});
+                } else {
+                    typedef O o8 __attribute__((ext_vector_type(8)));
+                    const o8 h = {from_f32<O>(v[0]), from_f32<O>(v[1]), from_f32<O>(v[2]), from_f32<O>(v[3]),
+                                  from_f32<O>(v[4]), from_f32<O>(v[5]), from_f32<O>(v[6]), from_f32<O>(v[7])};
+                    out = __builtin_bit_cast(u32x4, h);
+                }
                 if (i0 + row < m)
-                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(yb + (size_t)(i0 + row) * (size_t)n * sizeof(O) + pc * 16));
+                    __builtin_nontemporal_store(out, reinterpret_cast<u32x4*>(yb + (size_t)(i0 + row) * (size_t)n * sizeof(O) + pc * 16));
             }
         }
+        j += shares;
     }
 }
 
@@ -380,41 +438,93 @@ void build_group_plan(bsr_matrix* W, const int32_t* ptr, const int32_t* idx, siz
     W->grp_blocks = 0;
     W->grp_host.clear();
     if (W->bs_r != 64 || W->bs_c != 64 || (W->dtype != BSR_F16 && W->dtype != BSR_BF16) || W->R <= 0 || W->nnzb <= 0) return;
+    if (W->nnzb >= ((int64_t)1 << 19) || W->C >= (1 << 24)) return;   // a record holds 32-bit byte offsets of tiles
     const int R = W->R;
     const int32_t* order = W->staging.data();         // block-rows by stored-block count, longest first: the plan's slot order
     auto count = [&](int r) { return ptr[r + 1] - ptr[r]; };
     const int min_count = W->env_tune.variant == 5 && W->env_tune.b > 0 ? W->env_tune.b : kHeavyMin;
     int max_groups = W->env_tune.variant == 5 && W->env_tune.nw > 0 ? W->env_tune.nw : kMaxGroups;
     max_groups = std::min(max_groups, kMaxGroups);
-    int H = 0;
-    while (H < R && H < kG * max_groups && count(order[H]) >= min_count) ++H;
-    if (H == 0) return;
-    const int n_groups = (H + kG - 1) / kG;
-    // deal the rows out longest first, each to the group with the fewest blocks that still has room
-    std::vector<std::vector<int>> members((size_t)n_groups);
+    int cand = 0;
+    while (cand < R && cand < kG * max_groups && count(order[cand]) >= min_count) ++cand;
+    if (cand == 0) return;
+    const int n_groups = std::min(max_groups, (cand + kG - 1) / kG);
+    // A wavefront multiplies one block-row, or a share of one: wavefronts that no row needs go, one at a time,
+    // to the row with the most blocks per wavefront (while that is more than one block), and the kernel adds
+    // up the results of a row's wavefronts.
+    const int H = std::min(cand, kG * n_groups);
+    std::vector<int> shares((size_t)H, 1);
+    for (int spare = kG * n_groups - H; spare > 0; --spare) {
+        int best = -1;
+        for (int s = 0; s < H; ++s)
+            if (shares[(size_t)s] < kG && count(order[s]) > shares[(size_t)s] &&
+                (best < 0 || (int64_t)count(order[s]) * shares[(size_t)best] > (int64_t)count(order[best]) * shares[(size_t)s]))
+                best = s;
+        if (best < 0) break;
+        ++shares[(size_t)best];
+    }
+    // deal the rows out longest first, each to the group with the fewest blocks that has wavefronts left for
+    // its shares (for fewer shares, if no group has that many left)
+    struct member { int row, shares; };
+    std::vector<std::vector<member>> members((size_t)n_groups);
     std::vector<int64_t> load((size_t)n_groups, 0);
+    std::vector<int> room((size_t)n_groups, kG);
     for (int s = 0; s < H; ++s) {
+        int want = shares[(size_t)s];
+        want = std::min(want, *std::max_element(room.begin(), room.end()));
         int best = -1;
         for (int q = 0; q < n_groups; ++q)
-            if ((int)members[(size_t)q].size() < kG && (best < 0 || load[(size_t)q] < load[(size_t)best])) best = q;
-        members[(size_t)best].push_back(order[s]);
+            if (room[(size_t)q] >= want && (best < 0 || load[(size_t)q] < load[(size_t)best])) best = q;
+        members[(size_t)best].push_back({order[s], want});
+        room[(size_t)best] -= want;
         load[(size_t)best] += count(order[s]);
         W->grp_blocks += count(order[s]);
     }
     std::vector<int32_t> desc((size_t)n_groups * kDescWords, 0), recs;
     for (int q = 0; q < n_groups; ++q) {
-        // rows of the group longest first (the members were dealt out in that order): wavefront j takes row j
-        std::vector<int32_t> rows(kG, -1);
-        for (size_t j = 0; j < members[(size_t)q].size(); ++j) rows[j] = members[(size_t)q][j];
+        // Order of the group's rows over its wavefronts (the shares of a row next to each other): wavefront j
+        // runs on SIMD j mod 4; of all orders, the first that leaves the busiest SIMD the fewest blocks.
+        std::vector<member>& mem = members[(size_t)q];
+        std::vector<int> perm(mem.size()), best_perm;
+        std::iota(perm.begin(), perm.end(), 0);
+        int64_t best_cost = -1;
+        do {
+            int64_t simd[4] = {0, 0, 0, 0};
+            int j = 0;
+            for (int i : perm)
+                for (int sh = 0; sh < mem[(size_t)i].shares; ++sh, ++j) {
+                    const int c = count(mem[(size_t)i].row), n = mem[(size_t)i].shares;
+                    simd[j & 3] += c / n + (sh < c % n ? 1 : 0);
+                }
+            const int64_t cost = *std::max_element(simd, simd + 4);
+            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_perm = perm; }
+        } while (std::next_permutation(perm.begin(), perm.end()));
+        // rows[j] = block-row of wavefront j; first[i], n[i] = the wavefronts of the i-th row in this order
+        std::vector<int32_t> rows(8, -1);
+        struct span { int row, first, n; };
+        std::vector<span> spans;
+        {
+            int j = 0;
+            for (int i : best_perm) {
+                spans.push_back({mem[(size_t)i].row, j, mem[(size_t)i].shares});
+                for (int sh = 0; sh < mem[(size_t)i].shares; ++sh) rows[(size_t)j++] = mem[(size_t)i].row;
+            }
+        }
         int32_t* d = desc.data() + (size_t)q * kDescWords;
-        for (int j = 0; j < kG; ++j) d[j] = rows[(size_t)j];
+        for (int j = 0; j < 8; ++j) d[j] = rows[(size_t)j];
         d[8] = (int32_t)(recs.size() / kRec);
-        // the group's stored blocks as (block-column, row of the group, stored-block number), by column
-        // (storage order inside a block-row is free, and a row may store a column twice)
+        // the group's stored blocks as (block-column, wavefront, stored-block number), by column (storage
+        // order inside a block-row is free, and a row may store a column twice); the blocks of a row go to
+        // its wavefronts in turn, in column order
         struct entry { int32_t col, j, p; };
         std::vector<entry> all;
-        for (size_t j = 0; j < rows.size(); ++j)
-            for (int32_t p = rows[j] < 0 ? 0 : ptr[rows[j]]; rows[j] >= 0 && p < ptr[rows[j] + 1]; ++p) all.push_back({idx[p], (int32_t)j, p});
+        for (const span& sp : spans) {
+            std::vector<entry> mine;
+            for (int32_t p = ptr[sp.row]; p < ptr[sp.row + 1]; ++p) mine.push_back({idx[p], 0, p});
+            std::stable_sort(mine.begin(), mine.end(), [](const entry& a, const entry& b) { return a.col < b.col; });
+            for (size_t o = 0; o < mine.size(); ++o) mine[o].j = sp.first + (int32_t)(o % (size_t)sp.n);
+            all.insert(all.end(), mine.begin(), mine.end());
+        }
         std::stable_sort(all.begin(), all.end(), [](const entry& a, const entry& b) { return a.col < b.col; });
         // windows: X tile of a column, then its blocks; a column that does not fit what is left of the
         // window opens the next one, and a column with more than kWin-1 blocks continues there
@@ -431,23 +541,42 @@ void build_group_plan(bsr_matrix* W, const int32_t* ptr, const int32_t* idx, siz
             }
             rc[1] = (int32_t)(xcols.size() + wb.size()) | ((int32_t)xcols.size() << 4);
             int t = kRecTilesAt;
-            for (int32_t c : xcols) rc[t++] = (int32_t)(0x80000000u | (uint32_t)c);
-            for (const auto& b : wb) rc[t++] = b.p;
+            for (int32_t c : xcols) rc[t++] = (int32_t)((uint32_t)c * 128u);
+            for (const auto& b : wb) rc[t++] = (int32_t)((uint32_t)b.p * (uint32_t)kTileBytes);
             recs.insert(recs.end(), rc, rc + kRec);
             xcols.clear();
             wb.clear();
         };
-        size_t at = 0;
-        while (at < all.size()) {
+        // columns as runs of `all`, a column with more than kWin-1 blocks cut into several (each stages X again)
+        struct run { size_t at; int n; };
+        std::vector<run> runs;
+        for (size_t at = 0; at < all.size();) {
             size_t end = at;
             while (end < all.size() && all[end].col == all[at].col) ++end;
-            while (at < end) {
+            for (; at < end; at += (size_t)std::min<size_t>(end - at, (size_t)(kWin - 1)))
+                runs.push_back({at, (int)std::min<size_t>(end - at, (size_t)(kWin - 1))});
+        }
+        // a window takes the first run not yet placed, then, from the kLookAhead runs behind it, whatever
+        // fills it best (the largest that fits, the earliest among equals): full windows mean fewer barriers
+        // and more bytes on their way, and the groups still walk the block-columns at about the same pace
+        std::vector<char> placed(runs.size(), 0);
+        for (size_t first = 0; first < runs.size(); ++first) {
+            if (placed[first]) continue;
+            auto take = [&](size_t r) {
+                placed[r] = 1;
+                xcols.push_back(all[runs[r].at].col);
+                for (int i = 0; i < runs[r].n; ++i) wb.push_back({all[runs[r].at + (size_t)i].j, all[runs[r].at + (size_t)i].p, (int32_t)xcols.size() - 1});
+            };
+            take(first);
+            for (;;) {
                 const int room = kWin - (int)(xcols.size() + wb.size());
-                const int want = (int)std::min<size_t>(end - at, (size_t)(kWin - 1));
-                if (room < 1 + want) { close(); continue; }
-                xcols.push_back(all[at].col);
-                for (int i = 0; i < want; ++i, ++at) wb.push_back({all[at].j, all[at].p, (int32_t)xcols.size() - 1});
+                size_t best = runs.size();
+                for (size_t r = first + 1; r < runs.size() && r <= first + (size_t)kLookAhead; ++r)
+                    if (!placed[r] && 1 + runs[r].n <= room && (best == runs.size() || runs[r].n > runs[best].n)) best = r;
+                if (best == runs.size()) break;
+                take(best);
             }
+            close();
         }
         close();
         d[9] = (int32_t)(recs.size() / kRec) - d[8];

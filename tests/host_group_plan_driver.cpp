@@ -2,11 +2,14 @@
 // patterns it builds the groups and their window records with the library's own host code and verifies what
 // the kernel relies on:
 //   - the grouped block-rows are exactly the leading grp_slots slots of the longest-first order, each in one
-//     group, at most 8 per group, longest first; every one stores at least the minimum number of blocks;
-//   - every stored block of a grouped row appears exactly once in the records, counted under its own row of
-//     the group, pointing at an X tile of the same window whose block-column is the block's;
-//   - a window holds 2..6 tiles, X tiles first, then the stored blocks sorted by row of the group; its counts
-//     add up; three windows in a row fit the 19-slot ring;
+//     group, on one wavefront or on several that follow each other (a long row is cut into shares); every one
+//     stores at least the minimum number of blocks, and every such row up to 16 is grouped; no
+//     group is empty, none has more than 8 wavefronts;
+//   - every stored block of a grouped row appears exactly once in the records, counted under a wavefront of
+//     its own row, pointing at an X tile of the same window whose block-column is the block's; the shares of
+//     a row differ by at most one block;
+//   - a window holds 2..6 tiles, X tiles first, then the stored blocks sorted by wavefront; its counts add
+//     up; three windows in a row fit the 19-slot ring; tiles are named by byte offset;
 //   - the plan fits the words bsr_workspace_size() promises for it.
 // Build: hipcc --offload-arch=gfx950 -O1 -std=c++17 -I include -I paper_2007_13055_amd/csrc \
 //        tests/host_group_plan_driver.cpp paper_2007_13055_amd/csrc/bsr_mfma_group.hip -o driver
@@ -56,12 +59,13 @@ int main()
         W.row_order = fake_ws.data();                    // only used to form device addresses, never read
         size_t words = order_words;
         build_group_plan(&W, ptr.data(), idx.data(), &words);
-        int expect = 0;
-        while (expect < R && expect < max_rows && ptr[order[expect] + 1] - ptr[order[expect]] >= min_count) ++expect;
-        CHECK(W.grp_slots == expect);
+        int cand = 0;
+        while (cand < R && cand < max_rows && ptr[order[cand] + 1] - ptr[order[cand]] >= min_count) ++cand;
+        const int expect = W.grp_slots;
+        CHECK(expect == cand);
         if (expect == 0) { CHECK(W.grp_n == 0 && words == order_words); continue; }
         ++plans;
-        CHECK(W.grp_n == (expect + 7) / 8);
+        CHECK(W.grp_n >= 1 && W.grp_n <= (max_rows + 7) / 8 && W.grp_n <= expect);
         CHECK(words - order_words <= group_plan_words(R, 64, 64, nnzb));
         const int32_t* desc = W.grp_host.data();
         const int32_t* recs = W.grp_host.data() + W.grp_host_recs_at;
@@ -74,14 +78,14 @@ int main()
         for (int g = 0; g < W.grp_n; ++g) {
             const int32_t* d = desc + (size_t)g * 16;
             bool ended = false;
-            int prev_count = 1 << 30;
+            std::vector<int> share_blocks(8, 0);
             for (int j = 0; j < 8; ++j) {
                 if (d[j] < 0) { ended = true; continue; }
-                CHECK(!ended && d[j] < R);                 // rows fill a group from the front, longest first
-                const int cnt = ptr[d[j] + 1] - ptr[d[j]];
-                CHECK(cnt <= prev_count);
-                prev_count = cnt;
-                ++row_seen[(size_t)d[j]];
+                CHECK(!ended && d[j] < R);                 // the wavefronts fill a group from the front
+                if (j == 0 || d[j - 1] != d[j]) {
+                    for (int i = 0; i < j; ++i) CHECK(d[i] != d[j]);   // a row's wavefronts follow each other
+                    ++row_seen[(size_t)d[j]];
+                }
             }
             CHECK(d[0] >= 0);
             CHECK(d[8] == next_rec && d[9] >= 1);
@@ -94,15 +98,18 @@ int main()
                 CHECK(prev2 + prev + nt <= 19);
                 prev2 = prev; prev = nt;
                 int sum = 0, at = 0;
-                for (int i = 0; i < nx; ++i) CHECK(rc[4 + i] < 0 && (rc[4 + i] & 0x7fffffff) < C);
+                for (int i = 0; i < nx; ++i) CHECK(rc[4 + i] >= 0 && rc[4 + i] % 128 == 0 && rc[4 + i] / 128 < C);   // byte offset into a row of X
                 for (int j = 0; j < 8; ++j) {
                     const int c = (rc[0] >> (4 * j)) & 15;
                     sum += c;
                     for (int q = 0; q < c; ++q, ++at) {    // the window's stored blocks come sorted by row of the group
                         CHECK(at < nb);
-                        const int p = rc[4 + nx + at], xi = (rc[2] >> (4 * at)) & 15, r = d[j];
+                        const uint32_t code = (uint32_t)rc[4 + nx + at];      // byte offset into block_data
+                        CHECK(code % 8192u == 0);
+                        const int p = (int)(code / 8192u), xi = (rc[2] >> (4 * at)) & 15, r = d[j];
+                        ++share_blocks[(size_t)j];
                         CHECK(r >= 0 && p >= ptr[r] && p < ptr[r + 1] && xi < nx);
-                        CHECK((rc[4 + xi] & 0x7fffffff) == idx[p]);
+                        CHECK(rc[4 + xi] / 128 == idx[p]);
                         ++blk_seen[(size_t)p];
                         ++blocks;
                     }
@@ -111,6 +118,12 @@ int main()
                 for (int i = nb; i < 8; ++i) CHECK(((rc[2] >> (4 * i)) & 15) == 0);
                 for (int i = nt; i < 12; ++i) CHECK(rc[4 + i] == 0);
             }
+            for (int j = 0; j < 8; ++j)                    // shares of a row: equal up to one block, all the row's blocks
+                if (d[j] >= 0 && (j == 0 || d[j - 1] != d[j])) {
+                    int lo = 1 << 30, hi = 0, sum = 0;
+                    for (int i = j; i < 8 && d[i] == d[j]; ++i) { lo = std::min(lo, share_blocks[(size_t)i]); hi = std::max(hi, share_blocks[(size_t)i]); sum += share_blocks[(size_t)i]; }
+                    CHECK(hi - lo <= 1 && sum == ptr[d[j] + 1] - ptr[d[j]]);
+                }
         }
         CHECK(blocks == W.grp_blocks);
         for (int s = 0; s < R; ++s) {

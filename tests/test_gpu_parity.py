@@ -468,15 +468,17 @@ def test_stripe_kernel_variant(oracle_mod, monkeypatch, extra, dtype, out):
 @pytest.mark.parametrize("extra", ["", ",b=1", ",b=3", ",b=1,nw=1"])
 @pytest.mark.parametrize("dtype,out", [("f16", "f16"), ("bf16", "bf16"), ("f16", "f32"), ("bf16", "f32")])
 def test_group_kernel_variant(oracle_mod, monkeypatch, extra, dtype, out):
-    """variant 5: 64x64 blocks of a 16-bit type; the longest block-rows in groups of up to 8 that walk the union
-    of their block-columns, the other block-rows through the tile kernel.  Long, short, single-block and empty
+    """variant 5: 64x64 blocks of a 16-bit type; the longest block-rows in groups of up to 8 wavefronts (a row on
+    one, or cut into shares for several whose results are added) that walk the union of their block-columns,
+    the other block-rows through the tile kernel.  Long, short, single-block and empty
     block-rows, more long rows than the groups hold, block-columns with 1 to 8 blocks, ragged m; b = fewest
     blocks of a grouped row (default 8), nw = groups at most."""
     monkeypatch.setenv("BSR_SPMM_TUNE", "variant=5" + extra)
     cases = [(5, np.array([3, 0, 9, 1])),
              (64, np.array([12, 12, 11, 12, 10, 12, 12, 9, 1, 0, 2])),            # a heavy group with full steps
              (130, np.array([0, 1, 2, 3, 20, 5, 0, 17, 9, 1, 1, 1, 1, 1, 1, 1, 1, 1, 4])),
-             (700, np.array([20, 18, 1, 0, 0, 7, 3, 3, 2, 1, 1, 15, 6]))]
+             (700, np.array([20, 18, 1, 0, 0, 7, 3, 3, 2, 1, 1, 15, 6])),
+             (200, np.array([19, 16, 1, 0]))]                                     # two long rows cut into shares for 8 wavefronts
     for m, counts in cases:
         C = 20
         p = wl.make_problem("grp", m, C * 64, counts.shape[0] * 64, 64, 64, dtype, out, ("counts", counts),
