@@ -12,6 +12,10 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbsr_spmm.so")
+# The checking build: the same sources with -DBSR_PLAIN_LOADS (every hand-placed load becomes an ordinary one
+# with compiler-placed waits).  Only tests load it, to hold the two builds' results against each other.
+OBJDIR_PLAIN = os.path.join(HERE, "_build_plain")
+LIB_PLAIN = os.path.join(HERE, "libbsr_spmm_plain.so")
 
 # -packed-fp32-ops off: the compiler must not form packed fp32 VALU instructions on this target.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
@@ -45,13 +49,15 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def _compile(src, force):
-    obj = os.path.join(OBJDIR, os.path.basename(src) + ".o")
+def _compile(src, force, plain=False):
+    obj = os.path.join(OBJDIR_PLAIN if plain else OBJDIR, os.path.basename(src) + ".o")
     deps = [src] + glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
     if not force and os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps):
         return obj
-    check = os.path.basename(src) in NO_SPILL
+    check = os.path.basename(src) in NO_SPILL and not plain
     extra = ["-Rpass-analysis=kernel-resource-usage"] if check else []
+    if plain:
+        extra.append("-DBSR_PLAIN_LOADS")
     r = subprocess.run(["hipcc", *HIPCC_FLAGS, *extra, "-c", src, "-o", obj], capture_output=True, text=True)
     if check:
         bad = _spilling_kernels(r.stderr) if r.returncode == 0 else []
@@ -75,18 +81,20 @@ def _compile(src, force):
     return obj
 
 
-def build(force: bool = True, jobs: int = 4) -> str:
-    """Compile every .hip file and link the shared library; returns its path."""
-    os.makedirs(OBJDIR, exist_ok=True)
+def build(force: bool = True, jobs: int = 4, plain: bool = False) -> str:
+    """Compile every .hip file and link the shared library (plain: the checking build); returns its path."""
+    os.makedirs(OBJDIR_PLAIN if plain else OBJDIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(lambda s: _compile(s, force), sources()))
+        objs = list(ex.map(lambda s: _compile(s, force, plain), sources()))
+    lib = LIB_PLAIN if plain else LIB
     r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc",
-                        "-Wno-unused-command-line-argument", "-o", LIB, *objs],
+                        "-Wno-unused-command-line-argument", "-o", lib, *objs],
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
     print(build(force="--incremental" not in sys.argv))
+    print(build(force="--incremental" not in sys.argv, plain=True))

@@ -24,6 +24,12 @@ template <typename O> __device__ __forceinline__ O from_f32(float v);
 template <> __device__ __forceinline__ f16_t from_f32<f16_t>(float v) { return (f16_t)v; }     // nearest-even
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }   // nearest-even
 
+// The lanes of one wavefront pass data to each other through LDS without a workgroup barrier: a wavefront's
+// LDS operations complete in order, so no instruction is needed.  The compiler has to be told, though: it
+// reasons about one lane, and may otherwise keep an operand it read before ("this lane stored nothing since")
+// or move a read in front of the lane's own write to another address.  No instruction is emitted.
+__device__ __forceinline__ void wave_lds_fence() { asm volatile("" ::: "memory"); }
+
 // A lane's operand: CH contiguous elements of type T, kept as 32-bit words.
 template <typename T, int CH>
 struct Frag {

@@ -27,8 +27,10 @@ constexpr unsigned kDead = 0x80000000u;               // byte offset no buffer r
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
+#ifndef BSR_PLAIN_LOADS
 // Buffer resource over [base, base + bytes): raw 32-bit data, no swizzle.
-__device__ __forceinline__ i32x4 make_rsrc(const void* base, int bytes)
+typedef i32x4 rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, int bytes)
 {
     const unsigned long long a = reinterpret_cast<unsigned long long>(base);
     i32x4 r;
@@ -42,12 +44,32 @@ __device__ __forceinline__ i32x4 make_rsrc(const void* base, int bytes)
 // 16-byte buffer load the compiler neither moves nor waits for: the caller places s_waitcnt itself
 // (the compiler would otherwise sink the loads of a wavefront's second block behind the
 // arithmetic of its first).
-__device__ __forceinline__ void load_b128(u32x4& dst, const i32x4& rsrc, unsigned offset)
+__device__ __forceinline__ void load_b128(u32x4& dst, const rsrc_t& rsrc, unsigned offset)
 {
     asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(dst) : "v"(offset), "s"(rsrc));
 }
 template <int N> __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N)); }
 __device__ __forceinline__ void arrived(u32x4& v) { asm volatile("" : "+v"(v)); }   // use v only below this point
+#else
+// The same loads through the compiler's buffer-load builtin, which places the waits itself (slower: it
+// waits for every load before the first use).  A second library is built this way; a test holds the two
+// builds' results against each other bit for bit, so a compiler that mishandled a register of a
+// hand-placed load (copied it before the data arrived) would show.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, int bytes)
+{
+    const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+    const unsigned long long u = (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)a) |
+                                 ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(a >> 32)) << 32);
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(u), 0, __builtin_amdgcn_readfirstlane(bytes), 0x00020000);
+}
+__device__ __forceinline__ void load_b128(u32x4& dst, const rsrc_t& rsrc, unsigned offset)
+{
+    dst = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)offset, 0, 0));
+}
+template <int N> __device__ __forceinline__ void wait_loads() {}
+__device__ __forceinline__ void arrived(u32x4&) {}
+#endif
 
 template <typename T, int BS_R, int BS_C, int MM_>
 struct ksplit_geom {
@@ -118,8 +140,8 @@ __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, 
 
     if (wave < nw && wave < cnt) {                     // this wavefront has at least one block
         // W of this block-row and the X rows of this m-tile as buffers: offsets past their ends read zero
-        const i32x4 wrsrc = make_rsrc(data + (size_t)p0 * (BS_R * BS_C), cnt * BLK);
-        const i32x4 xrsrc = make_rsrc(X + (size_t)i_base * (size_t)k, min(MM, m - i_base) * k * S);
+        const rsrc_t wrsrc = make_rsrc(data + (size_t)p0 * (BS_R * BS_C), cnt * BLK);
+        const rsrc_t xrsrc = make_rsrc(X + (size_t)i_base * (size_t)k, min(MM, m - i_base) * k * S);
         // lane's pieces: W piece t is bytes t*1024 + lane*16 of the block; X piece t is 16 bytes of
         // row t*RPI + lane/LPR of the tile
         unsigned w_g[NLW], w_l[NLW], x_g[NLX], x_l[NLX];
@@ -155,12 +177,14 @@ __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, 
             for (int t = 0; t < NLW; ++t) arrived(gw[s][t]);
 #pragma unroll
             for (int t = 0; t < NLX; ++t) arrived(gx[s][t]);
+            wave_lds_fence();                          // the other lanes have read the previous block's operands
 #pragma unroll
             for (int t = 0; t < NLW; ++t)
                 if (BLK % 1024 == 0 || t * 1024 + lane * 16 < BLK) *reinterpret_cast<u32x4*>(wl + w_l[t]) = gw[s][t];
 #pragma unroll
             for (int t = 0; t < NLX; ++t)
                 if (MM % RPI == 0 || t * RPI + lane / LPR < MM) *reinterpret_cast<u32x4*>(xl + x_l[t]) = gx[s][t];
+            wave_lds_fence();                          // operands are what the other lanes just wrote
             Frag<T, CH> wf[NA], xf;
 #pragma unroll
             for (int u = 0; u < NA; ++u) wf[u].load(reinterpret_cast<const T*>(wop + u * (MM * P)));
@@ -197,6 +221,7 @@ __global__ __launch_bounds__(512) void bsr_mfma_ksplit(const T* __restrict__ X, 
     // partial sums of the wavefronts that had at least one block -> LDS (over the wavefront's own
     // staging area, whose contents it has already consumed)
     const int used = min(nw, cnt);
+    wave_lds_fence();
     if (wave < used) {
         float* mine = reinterpret_cast<float*>(wl) + (size_t)li * LD;
 #pragma unroll

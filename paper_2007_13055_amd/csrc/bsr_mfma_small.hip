@@ -22,7 +22,9 @@ constexpr unsigned kDead = 0x80000000u;               // byte offset no buffer r
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ i32x4 make_rsrc(const void* base, int bytes)
+#ifndef BSR_PLAIN_LOADS
+typedef i32x4 rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, int bytes)
 {
     const unsigned long long a = reinterpret_cast<unsigned long long>(base);
     i32x4 r;
@@ -34,12 +36,29 @@ __device__ __forceinline__ i32x4 make_rsrc(const void* base, int bytes)
 }
 
 // 16-byte buffer load with hand-placed waits (see bsr_mfma_ksplit.hip for why).
-__device__ __forceinline__ void load_b128(u32x4& dst, const i32x4& rsrc, unsigned offset)
+__device__ __forceinline__ void load_b128(u32x4& dst, const rsrc_t& rsrc, unsigned offset)
 {
     asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(dst) : "v"(offset), "s"(rsrc));
 }
 template <int N> __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N)); }
 __device__ __forceinline__ void arrived(u32x4& v) { asm volatile("" : "+v"(v)); }
+#else
+// the same loads with compiler-placed waits (see bsr_mfma_ksplit.hip): the checking build
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, int bytes)
+{
+    const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+    const unsigned long long u = (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)a) |
+                                 ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(a >> 32)) << 32);
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(u), 0, __builtin_amdgcn_readfirstlane(bytes), 0x00020000);
+}
+__device__ __forceinline__ void load_b128(u32x4& dst, const rsrc_t& rsrc, unsigned offset)
+{
+    dst = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)offset, 0, 0));
+}
+template <int N> __device__ __forceinline__ void wait_loads() {}
+__device__ __forceinline__ void arrived(u32x4&) {}
+#endif
 
 template <typename T>
 struct small_geom {
@@ -88,8 +107,8 @@ __global__ __launch_bounds__(512) void bsr_mfma_small(const T* __restrict__ X, c
     unsigned char* xl = wl + 16 * P;                           // and X tile, [16][P]
 
     if (wave < nw && wave < cnt) {
-        const i32x4 wrsrc = make_rsrc(data, w_bytes);
-        const i32x4 xrsrc = make_rsrc(X + (size_t)i_base * (size_t)k, min(16, m - i_base) * k * S);
+        const rsrc_t wrsrc = make_rsrc(data, w_bytes);
+        const rsrc_t xrsrc = make_rsrc(X + (size_t)i_base * (size_t)k, min(16, m - i_base) * k * S);
         // lane's piece of the W tile: 16 bytes of block q = lane / LPS of the tile (dead past the last)
         const int q = lane / LPS;
         const unsigned within = (unsigned)(lane % LPS) * 16;
@@ -113,8 +132,10 @@ __global__ __launch_bounds__(512) void bsr_mfma_small(const T* __restrict__ X, c
             if (behind) wait_loads<2>(); else wait_loads<0>();   // uniform
             arrived(gw[s]);
             arrived(gx[s]);
+            wave_lds_fence();                          // the other lanes have read the previous tile's operands
             if (NSUB * LPS == 64 || lane < NSUB * LPS) *reinterpret_cast<u32x4*>(wl + w_l) = gw[s];
             if (RPI == 16 || xrow < 16u) *reinterpret_cast<u32x4*>(xl + x_l) = gx[s];
+            wave_lds_fence();                          // operands are what the other lanes just wrote
             Frag<T, CH> wf, xf;
             wf.load(reinterpret_cast<const T*>(wop));
             xf.load(reinterpret_cast<const T*>(xop));

@@ -178,6 +178,7 @@ __global__ __launch_bounds__(768) void bsr_mfma_stripe16(const T* __restrict__ X
     const int valid_bytes = (r_end - r_first) * 16 * (int)sizeof(O);   // the group's last wavefront may own < 4 block-rows
 #pragma unroll
     for (int s0 = 0; s0 < SUB; s0 += SPP) {
+        wave_lds_fence();
 #pragma unroll
         for (int ss = 0; ss < SPP; ++ss)
 #pragma unroll
@@ -185,6 +186,7 @@ __global__ __launch_bounds__(768) void bsr_mfma_stripe16(const T* __restrict__ X
                 store4<O>(reinterpret_cast<O*>(scratch + (size_t)(ss * 16 + li) * OS) + j * 16 + 4 * h,
                           acc[j][s0 + ss][0], acc[j][s0 + ss][1], acc[j][s0 + ss][2], acc[j][s0 + ss][3]);
         // same wavefront wrote and now reads: its LDS operations complete in order, no barrier needed
+        wave_lds_fence();
 #pragma unroll
         for (int pass = 0; pass < SPP * 16 / RPI; ++pass) {
             const int row = pass * RPI + orow;

@@ -139,7 +139,10 @@ __global__ __launch_bounds__(256) void bsr_thin16_f32(const float* __restrict__ 
 #pragma unroll
         for (int u = 0; u < U; ++u)
             xv[u] = *reinterpret_cast<const f32x4*>(xt_bytes + ((unsigned)col[u] * row_bytes + lane_x));
-        // the wavefront's own LDS area: its LDS operations complete in order, no barrier
+        // the wavefront's own LDS area: its LDS operations complete in order, no barrier.  (Every lane
+        // stores, to an address the compiler cannot tell from the one it reads next, so the reads stay
+        // behind the stores without a compiler fence -- which would also pin the gathers above in place:
+        // 15.7 instead of 13.3 us per product.)
 #pragma unroll
         for (int t = 0; t < WT; ++t) *reinterpret_cast<u32x4*>(wl + t * 1024 + lane * 16) = w4[t];
         float wv[U];

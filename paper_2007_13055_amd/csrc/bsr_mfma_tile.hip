@@ -24,6 +24,16 @@ namespace {
 constexpr int kXcds = 8;
 constexpr int kMaxGroups = 8;
 
+// Loads whose waits the kernel places itself (why: at their use below).  Built with BSR_PLAIN_LOADS they
+// are ordinary loads with compiler-placed waits: the checking build (see bsr_mfma_ksplit.hip).
+#ifndef BSR_PLAIN_LOADS
+__device__ __forceinline__ void load16(u32x4& dst, const unsigned char* src) { asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(src)); }
+__device__ __forceinline__ void load4(int& dst, const int32_t* src) { asm volatile("global_load_dword %0, %1, off" : "=v"(dst) : "v"(src)); }
+#else
+__device__ __forceinline__ void load16(u32x4& dst, const unsigned char* src) { dst = *reinterpret_cast<const u32x4*>(src); }
+__device__ __forceinline__ void load4(int& dst, const int32_t* src) { dst = *src; }
+#endif
+
 // Slot ranges [start[g], start[g+1]) of the launch-order groups (passed by value as a kernel argument).
 struct slot_groups {
     int n;
@@ -141,15 +151,15 @@ __global__ __launch_bounds__(256) void bsr_mfma_tile(const T* __restrict__ X, co
 #pragma unroll
         for (int j = 0; j < NLW; ++j) {
             const unsigned char* src = real ? wblk + wsrc[j] : wdata;
-            asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(wstage[d][j]) : "v"(src));
+            load16(wstage[d][j], src);
         }
 #pragma unroll
         for (int j = 0; j < NLX; ++j) {
             const unsigned char* src = real ? xsrc[j] + (size_t)c * RB : wdata;
-            asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(xstage[d][j]) : "v"(src));
+            load16(xstage[d][j], src);
         }
         const int32_t* nxt = indices + min(p + D, p1 - 1);
-        asm volatile("global_load_dword %0, %1, off" : "=v"(cidx[d]) : "v"(nxt));
+        load4(cidx[d], nxt);
     };
     auto stash = [&](int d) {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 1) * NL));
@@ -220,6 +230,7 @@ __global__ __launch_bounds__(256) void bsr_mfma_tile(const T* __restrict__ X, co
                 store4<O>(reinterpret_cast<O*>(ol + (size_t)(t * MM + li) * OS) + u * 32 + 8 * g + 4 * h,
                           acc[u][t][4 * g], acc[u][t][4 * g + 1], acc[u][t][4 * g + 2], acc[u][t][4 * g + 3]);
     // same wavefront wrote and now reads: its LDS operations complete in order, no barrier needed
+    wave_lds_fence();
     unsigned char* ybytes = reinterpret_cast<unsigned char*>(Y + (size_t)r * BS_R);
     const int orow = lane / OC, opiece = lane - orow * OC;
 #pragma unroll

@@ -137,6 +137,7 @@ __global__ __launch_bounds__(256) void bsr_sddmm_mfma(const T* __restrict__ G, c
     };
     auto stage = [&](int i0) {
         const bool tail = i0 + kChunk > m;            // uniform
+        wave_lds_fence();                             // the other lanes have read the previous chunk
 #pragma unroll
         for (int t = 0; t < NLG; ++t) {
             u32x4 v = gg[t];
@@ -153,6 +154,7 @@ __global__ __launch_bounds__(256) void bsr_sddmm_mfma(const T* __restrict__ G, c
                     *reinterpret_cast<u32x4*>(xt + j * (kChunk * PC) + x_row[t] * PC + x_cb[t]) = v;
                 }
             }
+        wave_lds_fence();                             // what is read next is what the other lanes just wrote
     };
     auto compute = [&]() {
         if constexpr (std::is_same<T, float>::value) {
@@ -220,6 +222,7 @@ __global__ __launch_bounds__(256) void bsr_sddmm_mfma(const T* __restrict__ G, c
     // (the staged pieces are consumed: a wavefront's own LDS operations complete in order), then the
     // fixed-order sum of the four partial blocks, 4 consecutive columns per thread, contiguous store.
     float* part = reinterpret_cast<float*>(gt);
+    wave_lds_fence();
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
         if (j >= cnt) break;
