@@ -295,68 +295,75 @@ __global__ __launch_bounds__(768) void bsr_mfma_group(const T* __restrict__ X, c
         if (kRingWin == 3 && n_win > 1) issue(rv, 16, 1);
     }
 
-    int w3 = 0;                                       // w mod 3
-    for (int w = 0; w < n_win; ++w) {
-        if (producer) {
+    // The two kinds of wavefront run loops of their own and meet at one barrier per window.
+    if (producer) {
+        int w3 = 0;                                   // w mod 3
+        for (int w = 0; w < n_win; ++w) {
             const int next_tiles = kRingWin == 3 && w + 1 < n_win ? (__builtin_amdgcn_readlane(rv, 17) & 15) : 0;
             wait_all_but(loads_of(next_tiles));       // this wavefront's share of window w has landed
-        }
-        barrier();                                    // ... everybody's has, and everybody is done with window w-1
-        const int rv_next = read_records(w + 1);      // used in the next trip
-        if (producer) {
+            barrier();                                // ... everybody's has, and everybody is done with window w-1
+            const int rv_next = read_records(w + 1);  // used in the next trip
             // every 64 windows the half of the record area that was used up takes the records 64 .. 127 ahead
             // (loads complete in order, so they have landed, for everybody, many windows before they are read)
             if ((w & 63) == 0 && w > 0 && w + 64 < n_win) load_records((w >> 6) + 1);
             // the window kRingWin - 1 ahead takes the slots of window w-1
             if (w + kRingWin - 1 < n_win) issue(rv, 16 * (kRingWin - 1), w3 == 0 ? kRingWin - 1 : w3 - 1);
+            w3 = w3 == kRingWin - 1 ? 0 : w3 + 1;
+            rv = rv_next;
         }
-        const unsigned all_counts = (unsigned)__builtin_amdgcn_readlane(rv, 0);
-        const int info = __builtin_amdgcn_readlane(rv, 1);
-        const unsigned xis = (unsigned)__builtin_amdgcn_readlane(rv, 2);
-        const int nx = (info >> 4) & 15;
-        // this wavefront's blocks: how many, and how many belong to the wavefronts before it (the window's blocks are sorted by wavefront)
-        const int c = producer ? 0 : (int)((all_counts >> (4 * (wave & 7))) & 15u);
-        const unsigned below = all_counts & ((1u << (4 * (wave & 7))) - 1u);
-        const unsigned pairs = (below & 0x0f0f0f0fu) + ((below >> 4) & 0x0f0f0f0fu);
-        const int before = (int)((pairs * 0x01010101u) >> 24);
-        if (c > 0) {                                  // uniform
-            const unsigned char* wb = ring + w3 * (kWin * kTileBytes);
-            const unsigned char* wt = wb + (nx + before) * kTileBytes;       // the row's first block in this window
-            unsigned xsel = xis >> (4 * before);      // which X tile each of its blocks multiplies, 4 bits each
-            // fa / fb: k elements 0-31 / 32-63 of the block in turn.  While one half is multiplied the other
-            // half's operands are read: 8 LDS reads interleaved with the first 8 of the 16 MFMAs.
-            half_frag fa, fb;
-            fa.load(wt, wb + (xsel & 15u) * kTileBytes, f_off);
-            for (int i = 0; i < c; ++i) {
-                // behind the row's last block of the window the reads repeat that block's and are dropped
-                const bool more = i + 1 < c;
-                const unsigned char* wn = more ? wt + kTileBytes : wt;
-                const unsigned xnext = more ? xsel >> 4 : xsel;
-                __builtin_amdgcn_sched_barrier(0);
-                fb.load(wt, wb + (xsel & 15u) * kTileBytes, f_off ^ 64u);
-                multiply(fa);
+    } else {
+        int w3 = 0;
+        for (int w = 0; w < n_win; ++w) {
+            barrier();                                // window w has landed
+            const int rv_next = read_records(w + 1);
+            const unsigned all_counts = (unsigned)__builtin_amdgcn_readlane(rv, 0);
+            const int info = __builtin_amdgcn_readlane(rv, 1);
+            const unsigned xis = (unsigned)__builtin_amdgcn_readlane(rv, 2);
+            const int nx = (info >> 4) & 15;
+            // this wavefront's blocks: how many, and how many belong to the wavefronts before it (the window's blocks are sorted by wavefront)
+            const int c = (int)((all_counts >> (4 * wave)) & 15u);
+            const unsigned below = all_counts & ((1u << (4 * wave)) - 1u);
+            const unsigned pairs = (below & 0x0f0f0f0fu) + ((below >> 4) & 0x0f0f0f0fu);
+            const int before = (int)((pairs * 0x01010101u) >> 24);
+            if (c > 0) {                                  // uniform
+                const unsigned char* wb = ring + w3 * (kWin * kTileBytes);
+                const unsigned char* wt = wb + (nx + before) * kTileBytes;       // the row's first block in this window
+                unsigned xsel = xis >> (4 * before);      // which X tile each of its blocks multiplies, 4 bits each
+                // fa / fb: k elements 0-31 / 32-63 of the block in turn.  While one half is multiplied the other
+                // half's operands are read: 8 LDS reads interleaved with the first 8 of the 16 MFMAs.
+                half_frag fa, fb;
+                fa.load(wt, wb + (xsel & 15u) * kTileBytes, f_off);
+                for (int i = 0; i < c; ++i) {
+                    // behind the row's last block of the window the reads repeat that block's and are dropped
+                    const bool more = i + 1 < c;
+                    const unsigned char* wn = more ? wt + kTileBytes : wt;
+                    const unsigned xnext = more ? xsel >> 4 : xsel;
+                    __builtin_amdgcn_sched_barrier(0);
+                    fb.load(wt, wb + (xsel & 15u) * kTileBytes, f_off ^ 64u);
+                    multiply(fa);
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-                }
-                __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                fa.load(wn, wb + (xnext & 15u) * kTileBytes, f_off);
-                multiply(fb);
+                    for (int q = 0; q < 8; ++q) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    fa.load(wn, wb + (xnext & 15u) * kTileBytes, f_off);
+                    multiply(fb);
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    for (int q = 0; q < 8; ++q) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    wt = wn;
+                    xsel = xnext;
                 }
-                __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                wt = wn;
-                xsel = xnext;
             }
+            w3 = w3 == kRingWin - 1 ? 0 : w3 + 1;
+            rv = rv_next;
         }
-        w3 = w3 == kRingWin - 1 ? 0 : w3 + 1;
-        rv = rv_next;
     }
 
     // ---- epilogue: every wavefront's 64x64 fp32 result through LDS (the ring is free: no load is outstanding);
