@@ -19,7 +19,7 @@ constexpr int kRowDescWords = 32;
 constexpr int kRowDescColsAt = 4;                 // word index of the first inline block-column
 constexpr int kRowDescCols = kRowDescWords - kRowDescColsAt;
 constexpr int kMaxKsplitItems = 4096;             // the k-split kernel is used below this many (block-row, m-tile) items
-constexpr int kStripeChunkPairs = 6;              // the stripe kernel's pair table lists block-rows in chunks of this many pairs
+constexpr int kStripeChunkPairs = 3;              // the stripe kernel's pair table lists block-rows in chunks of this many pairs
 constexpr int kItemSlots = 4;                     // k-split work-item tables a handle keeps (one per recent m)
 
 // Development knobs, read from the environment variable BSR_SPMM_TUNE ("key=value,key=value"), and
