@@ -15,8 +15,11 @@
 // whole CHUNKS of kStripeChunkPairs pairs; a slot without a stored block ("dead") carries a byte
 // offset past the end of W, which a buffer load answers with zeros, and the index of an extra,
 // all-zero LDS panel for X.  So a chunk is always kStripeChunkPairs x (TM/16) MFMAs, the
-// compiler can schedule its LDS reads and MFMAs freely, and W for the next two block-rows is
-// already on its way (three register buffers) while one is multiplied.
+// compiler can schedule its LDS reads and MFMAs freely.  Chunks are short (3 pairs: the fewer slots a
+// chunk has, the fewer of them are dead), so most block-rows take two or more: W travels through
+// four register buffers, a pair per block-row in turn -- the chunk after next is loaded into the
+// buffer a multiply has just freed, and the first two chunks of the row after next into the pair a
+// finished row leaves behind.
 //
 // LDS layout of the stripe: one PANEL per block-column (TM rows x 32 bytes, panels PS bytes apart),
 // so the 16-row tiles of a lane's operand are at compile-time offsets from one address; the two
@@ -30,7 +33,7 @@ namespace {
 constexpr int kXcds = 8;
 constexpr int kRowsPerWave = 4;      // block-rows per wavefront: 4 x 16 columns = 64 outputs per row of Y
 constexpr int KP = kStripeChunkPairs;
-constexpr int kBufs = 3;             // W chunks in registers: one in use, two in flight
+constexpr int kBufs = 4;             // W chunks in registers: a pair per block-row in turn, the other pair filling for the row after next
 constexpr int kStageBatch = 8;       // 16-byte loads in flight per thread while the stripe is staged
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -97,8 +100,10 @@ __global__ __launch_bounds__(768) void bsr_mfma_stripe16(const T* __restrict__ X
 
     // first chunks of the first block-rows: in flight while the stripe is staged
 #pragma unroll
-    for (int j = 0; j < kBufs && j < kRowsPerWave; ++j)
-        if (q0[j] < q1[j]) load_chunk(j, q0[j]);      // uniform
+    for (int j = 0; j < 2; ++j) {                     // the first two chunks of the first two block-rows (uniform)
+        if (q0[j] < q1[j]) load_chunk(2 * j, q0[j]);
+        if (q0[j] + KP < q1[j]) load_chunk(2 * j + 1, q0[j] + KP);
+    }
 
     // ---- stage the stripe: TM rows x k columns, one contiguous piece of memory ----
     // chunk q (16 bytes) of the stripe lies in row q / cpr; the quotient comes from a multiply with
@@ -150,17 +155,24 @@ __global__ __launch_bounds__(768) void bsr_mfma_stripe16(const T* __restrict__ X
         }
     };
 
+    // Block-row j multiplies out of the buffer pair (2 (j mod 2), + 1) in turn: while one chunk is multiplied the
+    // chunk after next is loaded into the buffer just used, and when the row is done the pair takes the first two
+    // chunks of the row after next.
 #pragma unroll
     for (int j = 0; j < kRowsPerWave; ++j) {
-        const int buf = j % kBufs;
-        if (q0[j] < q1[j]) {                          // uniform: the block-row stores something
-            compute_chunk(buf, j);
-            for (int qb = q0[j] + KP; qb < q1[j]; qb += KP) {      // block-rows longer than one chunk
-                load_chunk(buf, qb);
-                compute_chunk(buf, j);
+        const int A = 2 * (j % 2), B = A + 1;
+        for (int qb = q0[j]; qb < q1[j]; qb += 2 * KP) {          // chunks qb (in A) and qb + KP (in B)
+            compute_chunk(A, j);
+            if (qb + 2 * KP < q1[j]) load_chunk(A, qb + 2 * KP);
+            if (qb + KP < q1[j]) {
+                compute_chunk(B, j);
+                if (qb + 3 * KP < q1[j]) load_chunk(B, qb + 3 * KP);
             }
         }
-        if (j + kBufs < kRowsPerWave && q0[j + kBufs] < q1[j + kBufs]) load_chunk(buf, q0[j + kBufs]);
+        if (j + 2 < kRowsPerWave) {
+            if (q0[j + 2] < q1[j + 2]) load_chunk(A, q0[j + 2]);
+            if (q0[j + 2] + KP < q1[j + 2]) load_chunk(B, q0[j + 2] + KP);
+        }
     }
 
     // Epilogue.  A lane holds, for row i = s*16 + li, columns (r_first + j)*16 + 4h .. +3: neighbouring
