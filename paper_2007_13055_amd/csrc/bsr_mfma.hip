@@ -204,7 +204,12 @@ bsr_status launch_mfma(const spmm_args& a, const tune_opts& tune)
         tt.b = 0;
         tt.nw = 0;
         if (tt.mt == 0) tt.mt = 1;
-        if (tt.a == 0) tt.a = 2;
+        if (tt.a == 0) {
+            // blocks in flight per workgroup: two pay only when the rows that are left still have a few blocks each
+            // (the 8192^3 power-law workload, 2.2 per row: 111.4 us with one against 112.7 with two)
+            const int64_t rows_left = a.W->R - a.W->grp_slots, blocks_left = a.W->nnzb - a.W->grp_blocks;
+            tt.a = blocks_left >= 4 * rows_left ? 2 : 1;
+        }
         return launch_mfma_tile(rest, tt);
     }
     if (variant == 2) return launch_mfma_ksplit(a, t);
