@@ -179,8 +179,8 @@ bsr_status launch_mfma(const spmm_args& a, const tune_opts& tune)
         else if (a.W->mean_row_blocks > 4.0) variant = 2;     // 16-row blocks the tile kernel does not take
         else variant = 1;
         // 64x64 16-bit blocks with a few block-rows that hold much of W: those rows in row groups (their X
-        // tiles shared through LDS), the rest through the tile kernel (126 against 136 us on the 8192^3
-        // power-law workload, 405 instead of 825 MB fetched)
+        // tiles shared through LDS), the rest through the tile kernel (112 against 135 us on the 8192^3
+        // power-law workload, 403 instead of 825 MB fetched)
         if (variant == 3 && t.mt == 0 && a.m >= 1024 && mfma_group_supports(a.W) && a.W->grp_blocks * 5 >= a.W->nnzb * 2)
             variant = 5;
         if (variant == 3 && t.mt == 0) {

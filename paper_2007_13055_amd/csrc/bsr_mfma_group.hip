@@ -60,7 +60,7 @@
 // Measured on the 8192^3 power-law workload (16 grouped rows = 573 of 819 blocks, 75 and 73 windows):
 // this kernel fetches about 220 MB from beyond L2 where the tile kernel fetches 601 MB for the same
 // rows, and takes about 65 us for them against 105 us; with the tile kernel for the other rows the
-// product takes 113-116 us instead of 135 us.  What bounds it: a workgroup streams 3.3 MB of tiles
+// product takes 111-116 us instead of 135 us.  What bounds it: a workgroup streams 3.3 MB of tiles
 // per 64 rows of X; with the multiplying switched off the kernel takes 50 us (a CU takes in about
 // 30 bytes per clock), with the loads switched off 51-55 us (per window the busiest SIMD multiplies
 // two blocks while the average is one), and the two overlap only partly behind one barrier per window.
