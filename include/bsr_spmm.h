@@ -188,7 +188,8 @@ bsr_status bsr_tune(bsr_matrix* W, int64_t m, const void* X_dev, void* Y_dev, bs
 
 /*
  * What bsr_tune() remembered for (m, y_dtype): settings_out = {kernel family (bsr_path), matrix-core
- * kernel variant (0 the library's choice, 1 direct, 2 k-split, 3 LDS tiles, 4 LDS stripe), wavefronts
+ * kernel variant (0 the library's choice, 1 direct, 2 k-split, 3 LDS tiles, 4 LDS stripe, 5 row groups for
+ * the longest block-rows and LDS tiles for the others), wavefronts
  * per workgroup, tile setting, two per-variant settings}, 0 = the kernel's default; us_out (may be
  * NULL) its measured microseconds per product.  BSR_ERR_UNSUPPORTED if nothing is remembered.
  */
