@@ -67,16 +67,6 @@ __global__ __launch_bounds__(768) void bsr_mfma_stripe16(const T* __restrict__ X
     const int r_first = group * rows_per_group + wave * kRowsPerWave;
     const int r_end = min(min((group + 1) * rows_per_group, R), r_first + kRowsPerWave);
 
-    // entry ranges of this wavefront's block-rows in the pair table, whole chunks each (rows past
-    // r_end get an empty range)
-    int q0[kRowsPerWave], q1[kRowsPerWave];
-#pragma unroll
-    for (int j = 0; j < kRowsPerWave; ++j) {
-        const int r = min(r_first + j, R - 1);
-        q0[j] = pair_ptr[r];
-        q1[j] = r_first + j < r_end ? pair_ptr[r + 1] : q0[j];
-    }
-
     // W through a buffer resource: a byte offset >= w_bytes (the dead slots) reads as zero
     const __amdgpu_buffer_rsrc_t wrsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(data), 0, (int)w_bytes, 0x00020000);
@@ -98,27 +88,23 @@ __global__ __launch_bounds__(768) void bsr_mfma_stripe16(const T* __restrict__ X
         }
     };
 
-    // first chunks of the first block-rows: in flight while the stripe is staged
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {                     // the first two chunks of the first two block-rows (uniform)
-        if (q0[j] < q1[j]) load_chunk(2 * j, q0[j]);
-        if (q0[j] + KP < q1[j]) load_chunk(2 * j + 1, q0[j] + KP);
-    }
-
     // ---- stage the stripe: TM rows x k columns, one contiguous piece of memory ----
     // chunk q (16 bytes) of the stripe lies in row q / cpr; the quotient comes from a multiply with
     // cpr_magic = floor(2^32 / cpr) + 1, exact for q < 2^16 (the stripe has at most 10240 chunks).
     // kStageBatch loads are issued before the first LDS write; past the end the last chunk is
     // simply copied again (same bytes to the same place).
+    // The first batch of loads goes out before anything else: it needs nothing but the workgroup's number, while
+    // the wavefront's ranges in the pair table and its first chunks of W are two dependent reads away.
+    int q0[kRowsPerWave], q1[kRowsPerWave];
     {
         const int cpr = RB / 16;                      // 16-byte chunks per row: 2 per block-column
         const int total = TM * cpr;
         const unsigned char* xb = reinterpret_cast<const unsigned char*>(X) + (size_t)i_base * (size_t)RB;
         const bool whole = i_base + TM <= m;          // uniform; else rows past m repeat row m-1, never stored
         const int step = (int)blockDim.x;
-        for (int base = tid; base < total; base += kStageBatch * step) {
-            u32x4 v[kStageBatch];
-            int dst[kStageBatch];
+        u32x4 v[kStageBatch];
+        int dst[kStageBatch];
+        auto fetch = [&](int base) {
 #pragma unroll
             for (int u = 0; u < kStageBatch; ++u) {
                 const int q = min(base + u * step, total - 1);
@@ -127,8 +113,34 @@ __global__ __launch_bounds__(768) void bsr_mfma_stripe16(const T* __restrict__ X
                 dst[u] = (cc >> 1) * PS + row * 32 + (((cc & 1) ^ ((row >> 2) & 1)) * 16);
                 v[u] = *reinterpret_cast<const u32x4*>(xb + src);
             }
+        };
+        auto put = [&]() {
 #pragma unroll
             for (int u = 0; u < kStageBatch; ++u) *reinterpret_cast<u32x4*>(lds + dst[u]) = v[u];
+        };
+        fetch(tid);                                   // every thread has a first batch (past the end: the last chunk again)
+        __builtin_amdgcn_sched_barrier(0);
+
+        // entry ranges of this wavefront's block-rows in the pair table, whole chunks each (rows past
+        // r_end get an empty range)
+#pragma unroll
+        for (int j = 0; j < kRowsPerWave; ++j) {
+            const int r = min(r_first + j, R - 1);
+            q0[j] = pair_ptr[r];
+            q1[j] = r_first + j < r_end ? pair_ptr[r + 1] : q0[j];
+        }
+
+        // first chunks of the first block-rows: in flight while the stripe is staged
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {                     // the first two chunks of the first two block-rows (uniform)
+            if (q0[j] < q1[j]) load_chunk(2 * j, q0[j]);
+            if (q0[j] + KP < q1[j]) load_chunk(2 * j + 1, q0[j] + KP);
+        }
+
+        put();
+        for (int base = tid + kStageBatch * step; base < total; base += kStageBatch * step) {
+            fetch(base);
+            put();
         }
         for (int z = tid; z < TM * 2; z += step) *reinterpret_cast<u32x4*>(lds + C * PS + z * 16) = u32x4{0u, 0u, 0u, 0u};
     }
