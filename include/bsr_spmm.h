@@ -145,7 +145,7 @@ bsr_status bsr_spmm(const bsr_matrix* W, int64_t m, const void* X_dev, void* Y_d
 
 /*
  * Scratch.  Some kernels need device memory beyond X, W and Y for the duration of one product:
- * the thin-block matrix-core path (bs_r = 16, bs_c = 1, fp32) first writes a transposed copy of
+ * for thin blocks (bs_r = 16, bs_c = 1, fp32) one matrix-core path first writes a transposed copy of
  * X, m*k floats, so that the columns of X that the stored blocks select (Background: the block's
  * column index picks the part of X) become contiguous rows.  The library does not allocate it.
  *   bsr_scratch_size  bytes such a product with m rows would use (0 when no kernel for this W
@@ -154,8 +154,11 @@ bsr_status bsr_spmm(const bsr_matrix* W, int64_t m, const void* X_dev, void* Y_d
  *                     back with NULL.  The memory stays owned by the caller and must outlive its
  *                     use; products that use it must not overlap in time on one handle (they
  *                     share it), i.e. keep them on one stream.
- * Without (enough) scratch BSR_PATH_AUTO uses the wavefront-reduction kernels for such W and
- * BSR_PATH_MFMA returns BSR_ERR_WORKSPACE.
+ * A thin-block W whose block-rows store their blocks in non-decreasing block-column order (k a
+ * multiple of 4, at most 64512) needs none: its product runs in one launch that gathers the columns
+ * from rows of X staged in LDS, and is preferred unless the block-rows are dense (more than 80 blocks
+ * per 1024 columns on average).  For any other thin-block W, without (enough) scratch BSR_PATH_AUTO
+ * uses the wavefront-reduction kernels and BSR_PATH_MFMA returns BSR_ERR_WORKSPACE.
  */
 bsr_status bsr_scratch_size(const bsr_matrix* W, int64_t m, size_t* bytes);
 bsr_status bsr_set_scratch(bsr_matrix* W, void* scratch_dev, size_t bytes);

@@ -616,7 +616,7 @@ static std::vector<tuned_choice> tune_candidates(const bsr_matrix* W, int64_t m)
     const bool thin = mfma_thin_supports(W);
     if (thin) {
         if (mfma_thinrow_supports(W) && m >= 8)
-            for (int a : {1, 2}) add(BSR_PATH_MFMA, 2, 0, 0, a, 0);
+            add(BSR_PATH_MFMA, 2, 0, 0, 0, 0);
         if (W->scratch && W->scratch_bytes >= mfma_thin_scratch_bytes(W, m) && m >= 16)
             for (int a : {4, 6, 8, 10, 12, 14, 16}) add(BSR_PATH_MFMA, 1, 0, 0, a, 0);
     } else if (mfma_small_supports(W)) {

@@ -96,6 +96,7 @@ struct bsr_matrix {
     // of 1024, [R][thin_nph + 1] (device); null when the kernel cannot take this W.
     const int32_t* thin_ph = nullptr;
     int32_t thin_nph = 0;
+    int32_t thin_max_run = 0;                // stored blocks of the longest (block-row, 1024 columns) run
     // Debug mode (BSR_SPMM_DEBUG=1 at bsr_create, bsr_debug.hip): the device arrays are re-checked before every product
     bool debug = false;
     size_t debug_words = 0;                  // words of the plan that never change after bsr_create

@@ -232,12 +232,15 @@ bsr_status launch_mfma_thin(const spmm_args& a, const tune_opts& tune)
 {
     const bsr_matrix* W = a.W;
     if (!mfma_thin_supports(W) || a.y_dtype != BSR_F32) return BSR_ERR_UNSUPPORTED;
-    // With enough scratch lent: the transposed copy of X, then the gather kernel (two launches, the faster
-    // way: 14 against 35 us on the 256 x 4096 x 4096 workload).  Without: one launch with the rows of X
-    // staged in LDS, when the plan allows it.  variant 1 / 2 ask for the one or the other.
+    // One launch with the rows of X staged in LDS when the plan allows it and the runs of a phase are short
+    // enough to be loaded ahead (12 against 13.3 us on the 256 x 4096 x 4096 workload, and no scratch).  Else,
+    // with enough scratch lent: the transposed copy of X, then the gather kernel (two launches).  variant 1 / 2
+    // ask for the one or the other.
     const bool lent = W->scratch && W->scratch_bytes >= mfma_thin_scratch_bytes(W, a.m);
-    if (tune.variant == 2 || (tune.variant != 1 && !lent && mfma_thinrow_supports(W)))
-        return mfma_thinrow_supports(W) ? launch_mfma_thinrow(a, tune) : BSR_ERR_UNSUPPORTED;
+    const bool rows_ok = mfma_thinrow_supports(W);
+    const bool rows_fit = rows_ok && W->nnzb <= (int64_t)80 * W->R * W->thin_nph;   // average run of a phase: at most 80 blocks
+    if (tune.variant == 2 || (tune.variant != 1 && rows_ok && (rows_fit || !lent)))
+        return rows_ok ? launch_mfma_thinrow(a, tune) : BSR_ERR_UNSUPPORTED;
     if (!lent) return BSR_ERR_WORKSPACE;
     return launch_thin_with_scratch(a, tune, W->scratch);
 }

@@ -7,26 +7,28 @@
 // Columns of a row-major X are strided (one element per row), so gathering them from memory moves a
 // cache line per element.  This is the paper's coalescing problem (Sections 4.4.2-4.4.3: reads are only
 // contiguous along the reduction axis of a block) at its extreme, a block that is one element wide.
-// Here the gather happens in LDS: a workgroup stages 16 whole rows of X, 256 columns (a PHASE) at a time,
+// Here the gather happens in LDS: a workgroup stages 16 whole rows of X, 1024 columns (a PHASE) at a time,
 // with coalesced 16-byte reads, and its wavefronts pick the columns their stored blocks name with 4-byte
-// LDS reads.  X is read row-major; no transposed copy exists anywhere.  The kernel with the transposed
-// copy in caller-lent scratch (bsr_mfma_thin.hip) is about 2.5 times faster and is preferred when the
-// scratch is there: here every 16 stored blocks cost a round of bookkeeping (cursor, clamps, loads)
-// that outweighs their four MFMAs.
+// LDS reads.  X is read row-major; no transposed copy exists anywhere.
 //
 // Plan (bsr_create): the stored blocks of every block-row must come in non-decreasing block-column
 // order (else this kernel is not used); per slot the plan keeps the positions where the block-columns
-// cross the multiples of 256, so the blocks of a (block-row, phase) are a contiguous run.
+// cross the multiples of 1024, so the blocks of a (block-row, phase) are a contiguous run.
 //
-// Workgroup = 16 rows of X x a set of 8*SPW slots; 12 wavefronts.  Wavefronts 8-11 only move X: each
-// takes 4 of the 16 rows through registers, six phases ahead, into two alternating LDS buffers.
-// Wavefronts 0-7 take SPW slots each; per phase and ROUND they take the next 16 stored blocks of each
-// slot: the block-columns and the blocks themselves (1 KiB, contiguous) arrive in a wavefront-private
-// LDS ring several rounds ahead (global_load_lds), and per 4 blocks one v_mfma_f32_16x16x4_f32 runs with
+// Workgroup = 16 rows of X x 16 slots; 16 wavefronts.  Wavefront w moves row w of the row group (4 KiB per
+// phase through registers into one of two LDS buffers, one phase ahead of its use) and multiplies slot w:
+// per phase its run of stored blocks, 4 blocks per v_mfma_f32_16x16x4_f32, with
 //   A (rows of the result = rows of X): lane l supplies X[i0 + l%16][column of block 4g + l/16] from LDS
 //   B (columns = the 16 outputs of the block-row): lane l supplies block_data[4g + l/16][l%16]
-// on two alternating accumulators per slot (a dependent MFMA would wait for its predecessor).
-// Entries past the end of a run multiply zeros: their B operand is replaced by zero.
+// on two alternating accumulators (a dependent MFMA would wait for its predecessor).  The blocks of a run
+// sit in registers, one dword per lane and MFMA (up to CAP MFMAs), and every register is re-loaded with the
+// next phase's run as soon as its MFMA has been issued: the only wait on memory inside a phase is the one at
+// its start, for loads that have had a whole phase to arrive.  The run's block-columns come with one load of
+// 64 (a CU takes one wavefront-wide load per 16 cycles whatever it carries, and the load instructions are what
+// bounds this kernel), go to a wavefront-private LDS area at the end of the phase before, and are read back
+// from there, four distinct values per MFMA.  Both are read through buffer resources over the run, so entries
+// past its end read as zero without branches (no traffic); a run longer than 4*CAP blocks takes extra passes
+// with loads of their own.  One barrier per phase.
 #include <algorithm>
 
 #include "bsr_mfma_common.h"
@@ -36,40 +38,35 @@ using namespace bsr_dev;
 namespace {
 
 constexpr int kRowsX = 16;                            // rows of X per workgroup
-constexpr int kPW = 256;                              // columns of X per phase
+constexpr int kPW = 1024;                             // columns of X per phase
 constexpr int kRS = kPW * 4 + 16;                     // LDS row stride in bytes: rows shift by 4 banks
 constexpr int kXBuf = kRowsX * kRS;
 constexpr int kNB = 2;                                // phase buffers: one in use, one being written
-constexpr int kConsumers = 8, kProducers = 4;
-constexpr int kChunk = 16;                            // stored blocks per chunk
-constexpr int kDepth = 6;                             // chunks a multiplying wavefront keeps in LDS: one in use, five on their way
-constexpr int kEntry = kChunk * 64 + 256;             // a chunk in LDS: its blocks (1 KiB), then 64 block-columns
-constexpr int kRing = kDepth * kEntry;                // per multiplying wavefront
-constexpr int kLds = kNB * kXBuf + kConsumers * kRing;
-constexpr int kThreads = 64 * (kConsumers + kProducers);
+constexpr int kWaves = 16;                            // = slots per workgroup = rows of X per workgroup
+constexpr int kMaxCap = 24;                           // MFMAs of a phase whose operands are loaded ahead, at most
+constexpr int kCArea = kMaxCap * 16;                  // a wavefront's block-columns of one phase, bytes
+constexpr int kLds = kNB * kXBuf + kWaves * 2 * kCArea;
+constexpr int kThreads = 64 * kWaves;
 constexpr int kMaxPhases = 63;                        // a slot's phase positions sit one per lane
-static_assert(kLds <= 160 * 1024 && kDepth % 2 == 0, "LDS; the ring holds whole rounds of 1 or 2 chunks");
-static_assert(kPW * 4 == 1024 && kRowsX == 4 * kProducers, "a moving wavefront takes 4 rows, one 1 KiB load each");
+static_assert(kLds <= 160 * 1024 && kWaves == kRowsX, "LDS; a wavefront moves one row");
 
-template <int N>
-__device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+// LDS writes of this wavefront done, then the workgroup's barrier (loads from memory stay in flight across it)
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
-
-template <int SPW>
+template <int CAP>
 __global__ __launch_bounds__(kThreads) void bsr_thin16_rows(const float* __restrict__ X, const float* __restrict__ data,
                                                            const int32_t* __restrict__ indices,
                                                            const int32_t* __restrict__ row_desc,
                                                            const int32_t* __restrict__ ph_ptr, float* __restrict__ Y,
-                                                           int m, int k, int n, int R, int nph, int n_rg, int n_set,
-                                                           unsigned data_bytes, unsigned index_bytes)
+                                                           int m, int k, int n, int R, int nph, int n_rg, int n_set)
 {
-    typedef __attribute__((address_space(3))) void lds_void;
-    typedef __attribute__((address_space(1))) const void glob_void;
+    static_assert(CAP % 4 == 0 && CAP <= kMaxCap, "MFMAs are skipped four at a time");
+    constexpr int NC = (4 * CAP + 63) / 64;           // loads of 64 block-columns per run
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lo = lane & 15, kk = lane >> 4;
 
     // Workgroup -> (row group, slot set).  The 8 XCDs take workgroups round-robin and have private L2s:
     // XCD x works on the row groups x%4, x%4 + 4, ... and the slot sets x/4, x/4 + 2, ..., so a row of X
@@ -81,171 +78,125 @@ __global__ __launch_bounds__(kThreads) void bsr_thin16_rows(const float* __restr
     if (ri >= rgs_here) return;
     const int rg = (x & 3) + 4 * ri, set = (x >> 2) + 2 * si;
     const int i0 = rg * kRowsX;
-    // The workgroups of an XCD start at about the same time and would walk the phases in step: all of them
-    // reading the same 1 KiB column range of their 16 rows, rows that are k*4 bytes apart and fall into the
-    // same L2 channel when k is a power of two.  Each workgroup therefore takes the phases in its own
-    // rotation: step i is phase (i + rot) mod nph (the order of a block-row's additions is free).
+    // The workgroups of an XCD start together and would walk the phases in step, all of them asking for the
+    // same column range of rows that are k*4 bytes apart.  Each workgroup therefore takes the phases in its
+    // own rotation: step s is phase (s + rot) mod nph (the order of a block-row's additions is free).
     const int rot = local % nph;
-    auto phase_of = [&](int i) { const int p = i + rot; return p >= nph ? p - nph : p; };
+    auto phase_of = [&](int s) { const int p = s + rot; return p >= nph ? p - nph : p; };
 
-    if (wave >= kConsumers) {
-        // ---- moving X: rows 4q .. 4q+3 of the row group, one load of 1 KiB per row and phase ----
-        const int q = wave - kConsumers;
-        const unsigned row_bytes = (unsigned)k * 4u;
-        const unsigned char* Xb = reinterpret_cast<const unsigned char*>(X);
-        const unsigned char* src[4];
+    // ---- moving X: this wavefront's row, four loads of 1 KiB per phase ----
+    const unsigned row_bytes = (unsigned)k * 4u;
+    const unsigned char* src = reinterpret_cast<const unsigned char*>(X) + (size_t)min(i0 + wave, m - 1) * row_bytes;
+    auto stage_load = [&](u32x4 (&r)[4], int s) __attribute__((always_inline)) {
+        // columns past k repeat the row's last 16 bytes (no stored block names them)
+        const unsigned cb = (unsigned)phase_of(s) * (kPW * 4u) + (unsigned)lane * 16u;
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) src[rr] = Xb + (size_t)min(i0 + 4 * q + rr, m - 1) * row_bytes;
-        // Rows travel through registers (16 bytes per lane and row), kAhead steps ahead, and are written to
-        // the step's buffer with 16-byte LDS writes.  (Loads that write LDS directly kept the LDS busy for
-        // about four times as long as these writes do, and the operand reads waited behind them.)
-        constexpr int kAhead = 6;
-        u32x4 st[kAhead][4];
-        auto load = [&](u32x4 (&r)[4], int i) __attribute__((always_inline)) {
-            // columns past k repeat the row's last 16 bytes (never read back)
-            const unsigned cb = min((unsigned)phase_of(i) * (kPW * 4u) + (unsigned)lane * 16u, row_bytes - 16u);
+        for (int q = 0; q < 4; ++q) r[q] = *reinterpret_cast<const u32x4*>(src + min(cb + q * 1024u, row_bytes - 16u));
+    };
+    auto stage_write = [&](const u32x4 (&r)[4], int s) __attribute__((always_inline)) {
+        unsigned char* dst = lds + (s & 1) * kXBuf + wave * kRS + lane * 16;
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) r[rr] = *reinterpret_cast<const u32x4*>(src[rr] + cb);
-        };
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<u32x4*>(dst + q * 1024) = r[q];
+    };
+
+    // The first two phases' rows go out at once; the second one's stays in flight behind the first run's
+    // loads, as in every later phase (a phase's row is always older than the run loaded after it).
+    u32x4 st0[4], st[4];
+    stage_load(st0, 0);
+
+    // ---- multiplying: slot set*16 + wave ----
+    const int slot = set * kWaves + wave;
+    // phase positions of the slot, one per lane: lane l holds position min(l, nph); a slot past R has empty runs
+    const int pp = slot < R ? ph_ptr[(size_t)slot * (size_t)(nph + 1) + min(lane, nph)] : 0;
+    stage_load(st, nph > 1 ? 1 : 0);
+    // the run of step s as a pair of buffer resources: its blocks (64 bytes each) and its block-columns
+    struct run_t { __amdgpu_buffer_rsrc_t w, i; int cnt; };
+    auto run_of = [&](int s) __attribute__((always_inline)) {
+        int e = 0, end = 0;
+        if (s < nph) {                                // uniform
+            const int ph = phase_of(s);
+            e = __builtin_amdgcn_readlane(pp, ph);
+            end = __builtin_amdgcn_readlane(pp, ph + 1);
+        }
+        run_t r;
+        r.cnt = max(end - e, 0);
+        r.w = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(data + (size_t)e * 16), 0, r.cnt * 64, 0x00020000);
+        r.i = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(indices + e), 0, r.cnt * 4, 0x00020000);
+        return r;
+    };
+    const int w_off = kk * 64 + lo * 4;               // lane's entry of MFMA 0; MFMA g: + 256 g
+    unsigned char* const c_area = lds + kNB * kXBuf + wave * (2 * kCArea);   // this wavefront's two areas (steps alternate)
+    auto c_load = [&](int (&cr)[NC], const run_t& r) __attribute__((always_inline)) {
 #pragma unroll
-        for (int d = 0; d < kAhead; ++d)
-            if (d < nph) load(st[d], d);
-        for (int base = 0; base < nph; base += kAhead) {
+        for (int j = 0; j < NC; ++j) cr[j] = __builtin_amdgcn_raw_buffer_load_b32(r.i, (64 * j + lane) * 4, 0, 0);
+    };
+    auto c_write = [&](const int (&cr)[NC], int s) __attribute__((always_inline)) {
 #pragma unroll
-            for (int d = 0; d < kAhead; ++d) {
-                const int i = base + d;
-                if (i < nph) {                        // uniform
-                    unsigned char* buf = lds + (i % kNB) * kXBuf + (4 * q) * kRS + lane * 16;
+        for (int j = 0; j < NC; ++j)
+            if (64 * j + 64 <= 4 * CAP || 64 * j + lane < 4 * CAP)
+                *reinterpret_cast<int*>(c_area + (s & 1) * kCArea + (64 * j + lane) * 4) = cr[j];
+    };
+
+    float wv[CAP];
+    int cr[NC];
+    run_t cur = run_of(0);
+    c_load(cr, cur);
 #pragma unroll
-                    for (int rr = 0; rr < 4; ++rr) *reinterpret_cast<u32x4*>(buf + rr * kRS) = st[d][rr];
-                    if (i + kAhead < nph) load(st[d], i + kAhead);
-                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                    wg_barrier();                     // step i is in its buffer; everybody is done with step i-1
+    for (int g = 0; g < CAP; ++g)
+        wv[g] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(cur.w, w_off + g * 256, 0, 0));
+    stage_write(st0, 0);
+    c_write(cr, 0);
+
+    f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+
+    for (int s = 0; s < nph; ++s) {
+        wg_barrier();                                 // step s is in its buffer; everybody is done with step s-1
+        if (s + 1 < nph) stage_write(st, s + 1);      // loaded a phase ago
+        if (s + 2 < nph) stage_load(st, s + 2);
+        const run_t nxt = run_of(s + 1);              // empty behind the last step
+        c_load(cr, nxt);
+        asm volatile("" ::: "memory");                // the row moves on before the multiplying starts, not behind it
+        // byte address of column 0 of this lane's row; the phase's first column sits at the buffer's start
+        const unsigned char* a_row = lds + (s & 1) * kXBuf + lo * kRS;
+        const unsigned char* c_at = c_area + (s & 1) * kCArea + kk * 4;
+        const int col0 = phase_of(s) * kPW;
+        int c[CAP];
+#pragma unroll
+        for (int g = 0; g < CAP; ++g) c[g] = *reinterpret_cast<const int*>(c_at + g * 16);
+#pragma unroll
+        for (int G = 0; G < CAP / 4; ++G) {
+            if (G * 16 < cur.cnt) {                   // uniform
+#pragma unroll
+                for (int g = 4 * G; g < 4 * G + 4; ++g) {
+                    // an entry past the run's end read 0 for its block (and 0 for its column: clamped)
+                    const unsigned rel = min((unsigned)(c[g] - col0), (unsigned)(kPW - 1));
+                    const float av = *reinterpret_cast<const float*>(a_row + rel * 4u);
+                    acc[g & 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, wv[g], acc[g & 1], 0, 0, 0);
                 }
             }
+#pragma unroll
+            for (int g = 4 * G; g < 4 * G + 4; ++g)
+                wv[g] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(nxt.w, w_off + g * 256, 0, 0));
         }
-        return;
-    }
-
-    // ---- multiplying wavefront: slots set*8*SPW + wave + 8*sl ----
-    const int lo = lane & 15, kk = lane >> 4;
-    const int slot0 = set * (kConsumers * SPW) + wave;
-    unsigned char* wr = lds + kNB * kXBuf + wave * kRing;
-    const unsigned char* Wb = reinterpret_cast<const unsigned char*>(data);
-
-    f32x4 acc[SPW][2];
-#pragma unroll
-    for (int s = 0; s < SPW; ++s) acc[s][0] = acc[s][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    // phase positions of the wavefront's slots, one per lane: lane l holds position min(l, nph)
-    int pp[SPW];
-#pragma unroll
-    for (int s = 0; s < SPW; ++s) {
-        const int slot = slot0 + kConsumers * s;
-        pp[s] = slot < R ? ph_ptr[(size_t)slot * (size_t)(nph + 1) + min(lane, nph)] : 0;
-    }
-    // The wavefront's work, step by step (a step = a phase in this workgroup's rotation): in every ROUND it
-    // takes the next chunk of 16 stored blocks of each of its SPW slots (a slot whose run is used up takes
-    // part with an empty chunk), so a round is straight-line code for SPW independent chunks, and a step has
-    // as many rounds as its longest run needs.  Two cursors walk the rounds: one issues their loads, the
-    // other, kRounds - 1 rounds behind, multiplies.
-    constexpr int kRounds = kDepth / SPW;             // rounds the ring holds
-    struct cursor { int step, r, rounds; };
-    auto run_of = [&](int step, int s, int& e, int& end) __attribute__((always_inline)) {
-        const int phase = phase_of(step);
-        e = __builtin_amdgcn_readlane(pp[s], phase);
-        end = __builtin_amdgcn_readlane(pp[s], phase + 1);
-    };
-    auto rounds_of = [&](int step) __attribute__((always_inline)) {
-        int most = 0;
-#pragma unroll
-        for (int s = 0; s < SPW; ++s) {
-            int e, end;
-            run_of(step, s, e, end);
-            most = max(most, end - e);
+        // a run longer than the registers hold: the rest with loads of its own, 4 blocks at a time
+        for (int b = 4 * CAP; b < cur.cnt; b += 4) {  // uniform
+            const float w = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(cur.w, w_off + b * 64, 0, 0));
+            const int cc = __builtin_amdgcn_raw_buffer_load_b32(cur.i, (b + kk) * 4, 0, 0);
+            const unsigned rel = min((unsigned)(cc - col0), (unsigned)(kPW - 1));
+            const float av = *reinterpret_cast<const float*>(a_row + rel * 4u);
+            acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, w, acc[0], 0, 0, 0);
         }
-        return (most + kChunk - 1) / kChunk;
-    };
-    auto advance = [&](cursor& c) __attribute__((always_inline)) {   // c.step == nph: no round left
-        if (c.step >= nph) return;
-        ++c.r;
-        while (c.r >= c.rounds) {
-            c.r = 0;
-            if (++c.step >= nph) return;
-            c.rounds = rounds_of(c.step);
-        }
-    };
-    // A round into ring position d: per slot the chunk's blocks (lane l: 16-byte piece l of the 1 KiB run) and
-    // 64 block-columns (lane l: block e + l), clamped to the arrays.  An empty chunk, and every chunk of the
-    // rounds behind the last one, reads the start of the arrays: every round issues 2*SPW loads, so "all but
-    // the youngest 2*SPW*(kRounds-1) have landed" always means the round in turn has.
-    const unsigned last_piece = data_bytes - 16u;
-    const int last_block = (int)(index_bytes >> 2) - 1;
-    auto issue = [&](const cursor& c, int d) __attribute__((always_inline)) {
-#pragma unroll
-        for (int s = 0; s < SPW; ++s) {
-            int e = 0, end = 0;
-            if (c.step < nph) run_of(c.step, s, e, end);
-            e = min(e + kChunk * c.r, max(end, 0));
-            unsigned char* dst = wr + (d * SPW + s) * kEntry;
-            const unsigned o = (unsigned)e * 64u + (unsigned)lane * 16u;
-            __builtin_amdgcn_global_load_lds((glob_void*)(Wb + min(o, last_piece)), (lds_void*)dst, 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((glob_void*)(indices + min(e + lane, last_block)), (lds_void*)(dst + kChunk * 64), 4, 0, 0);
-        }
-    };
-    cursor ci{-1, 0, 0};
-    advance(ci);
-    cursor cc = ci;
-#pragma unroll
-    for (int d = 0; d < kRounds - 1; ++d) {
-        issue(ci, d);
-        advance(ci);
-    }
-    int d_c = 0, d_i = kRounds - 1;
-
-    for (int step = 0; step < nph; ++step) {
-        wg_barrier();                                 // this step's columns of X are in their buffer
-        const unsigned char* a_base = lds + (step % kNB) * kXBuf + lo * kRS;
-        const int col0 = phase_of(step) * kPW;
-        while (cc.step == step) {                     // uniform
-            issue(ci, d_i);
-            advance(ci);
-            d_i = d_i + 1 == kRounds ? 0 : d_i + 1;
-            wait_vm<2 * SPW * (kRounds - 1)>();
-#pragma unroll
-            for (int s = 0; s < SPW; ++s) {
-                int e, end;
-                run_of(step, s, e, end);
-                const int cnt = min(max(end - e - kChunk * cc.r, 0), kChunk);   // blocks of this slot's chunk (may be none)
-                const unsigned char* ent = wr + (d_c * SPW + s) * kEntry;
-                const int col = *reinterpret_cast<const int*>(ent + kChunk * 64 + lo * 4);
-                const int rel = min(max(col - col0, 0), kPW - 1) * 4;         // byte offset of the column inside the phase
-                const unsigned char* b_base = ent + kk * 64 + lo * 4;
-#pragma unroll
-                for (int g = 0; g < kChunk / 4; ++g) {
-                    const int cb = __builtin_amdgcn_ds_bpermute((4 * g + kk) * 4, rel);
-                    const float av = *reinterpret_cast<const float*>(a_base + cb);
-                    float bv = *reinterpret_cast<const float*>(b_base + g * 256);
-                    bv = 4 * g + kk < cnt ? bv : 0.f;                         // entries past the run's end are zeros
-                    acc[s][g & 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc[s][g & 1], 0, 0, 0);
-                }
-            }
-            advance(cc);
-            d_c = d_c + 1 == kRounds ? 0 : d_c + 1;
-        }
+        c_write(cr, s + 1);                           // into the other area; read after the next barrier
+        cur = nxt;
     }
 
     // result of the MFMA: lane l holds rows 4*(l/16) + j (j = 0..3) of the row group, column l%16
+    if (slot < R) {
+        const int r = row_desc[(size_t)slot * kRowDescWords];
 #pragma unroll
-    for (int sl = 0; sl < SPW; ++sl) {
-        const int slot = slot0 + kConsumers * sl;
-        if (slot < R) {
-            const int r = row_desc[(size_t)slot * kRowDescWords];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int i = i0 + 4 * kk + j;
-                if (i < m) Y[(size_t)i * n + (size_t)r * 16 + lo] = acc[sl][0][j] + acc[sl][1][j];
-            }
+        for (int j = 0; j < 4; ++j) {
+            const int i = i0 + 4 * kk + j;
+            if (i < m) Y[(size_t)i * n + (size_t)r * 16 + lo] = acc[0][j] + acc[1][j];
         }
     }
 }
@@ -264,6 +215,7 @@ void build_thinrow_plan(bsr_matrix* W, const int32_t* ptr, const int32_t* idx, s
 {
     W->thin_ph = nullptr;
     W->thin_nph = 0;
+    W->thin_max_run = 0;
     if (W->bs_r != 16 || W->bs_c != 1 || W->dtype != BSR_F32 || W->R <= 0 || W->k < 4 || (W->k & 3) != 0) return;
     if (W->nnzb <= 0 || W->nnzb >= ((int64_t)1 << 25)) return;   // byte offsets into block_data are 32-bit
     if ((W->k + kPW - 1) / kPW > kMaxPhases) return;
@@ -276,15 +228,18 @@ void build_thinrow_plan(bsr_matrix* W, const int32_t* ptr, const int32_t* idx, s
     const size_t at = *words, end = (at + (size_t)R * (size_t)(nph + 1) + 63) & ~(size_t)63;
     W->staging.resize(end + 64, 0);
     order = W->staging.data();
+    int32_t longest = 0;
     for (int s = 0; s < R; ++s) {
         const int r = order[s];
         int32_t* out = W->staging.data() + at + (size_t)s * (size_t)(nph + 1);
         for (int ph = 0; ph <= nph; ++ph)
             out[ph] = (int32_t)(std::lower_bound(idx + ptr[r], idx + ptr[r + 1], ph * kPW) - idx);
         out[nph] = ptr[r + 1];
+        for (int ph = 0; ph < nph; ++ph) longest = std::max(longest, out[ph + 1] - out[ph]);
     }
     W->thin_ph = W->row_order + at;
     W->thin_nph = nph;
+    W->thin_max_run = longest;
     *words = end;
 }
 
@@ -293,27 +248,24 @@ bsr_status launch_mfma_thinrow(const spmm_args& a, const tune_opts& tune)
     const bsr_matrix* W = a.W;
     if (!mfma_thinrow_supports(W) || a.y_dtype != BSR_F32) return BSR_ERR_UNSUPPORTED;
     const int m = (int)a.m, n = (int)W->n, k = (int)W->k, R = W->R;
-    auto go = [&](auto spw_tag) -> bsr_status {
-        constexpr int SPW = decltype(spw_tag)::value;
-        const int n_rg = (m + kRowsX - 1) / kRowsX, n_set = (R + kConsumers * SPW - 1) / (kConsumers * SPW);
+    auto go = [&](auto cap_tag) -> bsr_status {
+        constexpr int CAP = decltype(cap_tag)::value;
+        const int n_rg = (m + kRowsX - 1) / kRowsX, n_set = (R + kWaves - 1) / kWaves;
         const int64_t grid = 8 * (int64_t)((n_rg + 3) / 4) * ((n_set + 1) / 2);
         if (grid >= ((int64_t)1 << 31)) return BSR_ERR_SHAPE;
-        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&bsr_thin16_rows<SPW>),
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&bsr_thin16_rows<CAP>),
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
         if (attr != hipSuccess) return BSR_ERR_HIP;
-        hipLaunchKernelGGL((bsr_thin16_rows<SPW>), dim3((unsigned)grid), dim3(kThreads), kLds, a.stream, (const float*)a.X,
+        hipLaunchKernelGGL((bsr_thin16_rows<CAP>), dim3((unsigned)grid), dim3(kThreads), kLds, a.stream, (const float*)a.X,
                            (const float*)W->data, W->indices, W->row_desc, W->thin_ph, (float*)a.Y, m, k, n, R,
-                           W->thin_nph, n_rg, n_set, (unsigned)(W->nnzb * 64), (unsigned)(W->nnzb * 4));
+                           W->thin_nph, n_rg, n_set);
         return hipGetLastError() == hipSuccess ? BSR_OK : BSR_ERR_HIP;
     };
-    // slots per multiplying wavefront: 2 unless that leaves most CUs without a workgroup
-    int spw = tune.a > 0 ? tune.a : 2;
-    if (tune.a <= 0) {
-        const int64_t wgs2 = (int64_t)((m + kRowsX - 1) / kRowsX) * ((R + 15) / 16);
-        if (wgs2 < W->n_cu && R > kConsumers) spw = 1;
-    }
-    if (spw <= 1) return go(std::integral_constant<int, 1>{});
-    return go(std::integral_constant<int, 2>{});
+    // MFMAs of a phase whose operands are loaded ahead (4 blocks each): enough for the average run and a
+    // quarter more; the few longer runs take their tails with loads of their own
+    const int64_t runs = (int64_t)R * W->thin_nph;
+    const int cap = tune.a > 0 ? tune.a : (int)((W->nnzb * 5 / 4 + runs - 1) / runs + 3) / 4;
+    if (cap <= 8) return go(std::integral_constant<int, 8>{});
+    if (cap <= 16) return go(std::integral_constant<int, 16>{});
+    return go(std::integral_constant<int, 24>{});
 }
-
-

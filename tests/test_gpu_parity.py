@@ -522,12 +522,12 @@ def test_group_kernel_config5_sampled_rows(oracle_mod, monkeypatch):
     assert np.array_equal(wl.round_to_storage(Yg32.astype(np.float32), "f16").astype(np.float64), Yg)
 
 
-@pytest.mark.parametrize("u", ["", "a=1", "a=2", "auto"])
+@pytest.mark.parametrize("u", ["", "a=1", "a=16", "a=24", "auto"])
 def test_thin_rows_staged_in_lds(oracle_mod, monkeypatch, u):
     """16x1 fp32 blocks on the matrix-core path in one launch: rows of X staged in LDS 1024 columns at a time,
-    the gather of columns done there (a = slots per multiplying wavefront).  One to five phases, a last phase
-    that is not full, block-rows with none, one, and several chunks of 32 blocks in a phase, ragged m, fewer
-    block-rows than a workgroup takes; no scratch is lent."""
+    the gather of columns done there (a = MFMAs of a phase whose operands sit in registers: 8, 16 or 24).  One to
+    five phases, a last phase that is not full, block-rows with none, one, and more blocks in a phase than the
+    registers hold (extra passes), ragged m, fewer block-rows than a workgroup takes; no scratch is lent."""
     import torch
     import paper_2007_13055_amd as lib
     path = MFMA
