@@ -47,6 +47,8 @@ size_t plan_bytes(int64_t R, int64_t nnzb, int32_t bs_r, int32_t bs_c, int64_t k
     b += sizeof(int32_t) * group_plan_words(R, bs_r, bs_c, nnzb);
     // thin blocks: the phase positions of every block-row
     b += sizeof(int32_t) * thinrow_plan_words(R, k, bs_r, bs_c);
+    // blocks of one row: the pairs by block-column and their range positions
+    b += sizeof(int32_t) * wide_plan_words(R, k, nnzb, bs_r, bs_c);
     b += 256;                                         // debug mode's result words
     return (b + 255) & ~(size_t)255;
 }
@@ -463,6 +465,7 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
     }
     build_group_plan(W, index_pointer_host, block_indices_host, &words);
     build_thinrow_plan(W, index_pointer_host, block_indices_host, &words);
+    build_wide_plan(W, index_pointer_host, block_indices_host, &words);
     size_t upload_words = words;
     {   // the per-m tables sit behind everything else, 256-byte aligned
         W->item_desc = const_cast<int32_t*>(W->row_order) + words;
@@ -523,6 +526,7 @@ bsr_status bsr_query_path(const bsr_matrix* W, int64_t m, bsr_path* path_out)
     else if (mfma_thin_supports(W) && m >= 32 && W->scratch && W->scratch_bytes >= mfma_thin_scratch_bytes(W, m))
         *path_out = BSR_PATH_MFMA;
     else if (mfma_thinrow_supports(W) && m >= 16) *path_out = BSR_PATH_MFMA;   // no scratch: rows of X staged in LDS
+    else if (mfma_wide_supports(W) && m >= 16) *path_out = BSR_PATH_MFMA;      // 1x16 blocks, by block-column
     else *path_out = BSR_PATH_WAVE;
     return BSR_OK;
 }
@@ -573,6 +577,7 @@ bsr_status run_product(const spmm_args& a, bsr_path path, const tune_opts& t)
     if (path == BSR_PATH_MFMA) {
         if (mfma_thin_supports(a.W)) return launch_mfma_thin(a, t);
         if (mfma_small_supports(a.W)) return launch_mfma_small(a, t);
+        if (mfma_wide_supports(a.W) && a.y_dtype == BSR_F32) return launch_mfma_wide(a, t);
         if (!mfma_supports(a.W)) return BSR_ERR_UNSUPPORTED;
         return launch_mfma(a, t);
     }

@@ -97,6 +97,15 @@ struct bsr_matrix {
     const int32_t* thin_ph = nullptr;
     int32_t thin_nph = 0;
     int32_t thin_max_run = 0;                // stored blocks of the longest (block-row, 1024 columns) run
+    // Blocks of one row (1x16 fp32: a thin W transposed) without duplicates (bsr_mfma_wide.hip): the stored blocks
+    // by (block-column, block-row) as pairs {byte offset of the block, block-row}, [nnzb][2]; the chunks (at most
+    // 16 pairs of one block-column inside one range of 256 block-rows) as {block-column, first pair, pairs, 0},
+    // listed per (range, wavefront), and the lists' starts, [8 * wide_nq + 1] (all device); null when the kernel
+    // cannot take this W.
+    const int32_t* wide_pairs = nullptr;
+    const int32_t* wide_chunks = nullptr;
+    const int32_t* wide_chunk_ptr = nullptr;
+    int32_t wide_nq = 0;
     // Debug mode (BSR_SPMM_DEBUG=1 at bsr_create, bsr_debug.hip): the device arrays are re-checked before every product
     bool debug = false;
     size_t debug_words = 0;                  // words of the plan that never change after bsr_create
@@ -216,6 +225,11 @@ bsr_status launch_mfma_thinrow(const spmm_args& a, const tune_opts& t);
 bool mfma_thinrow_supports(const bsr_matrix* W);
 void build_thinrow_plan(bsr_matrix* W, const int32_t* index_pointer_host, const int32_t* block_indices_host, size_t* words);
 size_t thinrow_plan_words(int64_t R, int64_t k, int32_t bs_r, int32_t bs_c);
+// bs_r = 1, bs_c = 16, fp32, no block stored twice: by block-column on the matrix cores, sums in LDS
+bsr_status launch_mfma_wide(const spmm_args& a, const tune_opts& t);
+bool mfma_wide_supports(const bsr_matrix* W);
+void build_wide_plan(bsr_matrix* W, const int32_t* index_pointer_host, const int32_t* block_indices_host, size_t* words);
+size_t wide_plan_words(int64_t R, int64_t k, int64_t nnzb, int32_t bs_r, int32_t bs_c);
 bsr_status launch_mfma_small(const spmm_args& a, const tune_opts& t);   // bs_r, bs_c in {8,16}, not both 16
 bool mfma_small_supports(const bsr_matrix* W);
 size_t mfma_thin_scratch_bytes(const bsr_matrix* W, int64_t m);   // bytes of the transposed copy of X

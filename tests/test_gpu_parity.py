@@ -589,6 +589,51 @@ def test_thin_rows_staged_in_lds_bitwise_and_fallback(oracle_mod):
     assert np.array_equal(Yg2, Yo)
 
 
+def test_wide_blocks_by_block_column(oracle_mod):
+    """1x16 fp32 blocks (a thin W transposed) on the matrix-core path: products by block-column, partial sums in
+    LDS.  Ragged m, n not a multiple of 4 or of the 256-column range, empty block-rows and block-columns, runs of
+    more than 16 blocks in a range, fewer block-columns than wavefronts, more than 512 of them (several batches of
+    runs), run-to-run bitwise equality, exact data, and a block stored twice (left to the other kernels)."""
+    import torch
+    import paper_2007_13055_amd as lib
+    for m, R, C in ((16, 40, 3), (70, 1000, 9), (257, 515, 40), (33, 4096, 64), (48, 300, 530), (600, 77, 12)):
+        rng = np.random.default_rng(3 * m + R)
+        counts = rng.integers(0, min(C, 30) + 1, size=R)
+        counts[0] = 0
+        counts[R // 2] = C
+        p = wl.make_problem("wide", m, C * 16, R, 1, 16, "f32", "f32", ("counts", counts), ("uniform", 1.0),
+                            ("uniform", 1.0), 900 + m)
+        Yo, So = oracle_of(oracle_mod, p)
+        W = lib.bsr_create(p.n, p.k, p.block_data, p.block_indices, p.index_pointer, dtype="f32")
+        assert lib.bsr_query_path(W, m) == MFMA and lib.bsr_query_path(W, 8) == WAVE
+        Yg, _ = gpu_product(p, path=MFMA, W=W)
+        check(Yg, Yo, So, p.tau, f"wide blocks m={m} R={R} C={C}")
+        Yg2, _ = gpu_product(p, path=MFMA, W=W)
+        assert np.array_equal(Yg, Yg2), "two runs differ: race"
+        Ya, _ = gpu_product(p, path=0, W=W)
+        assert np.array_equal(Ya, Yg)                              # the library's own choice is this kernel
+    q = wl.small_integer_problem(100, 40 * 16, 700, 1, 16, 0.3, seed=33)
+    Yo, So = oracle_of(oracle_mod, q)
+    Yg, _ = gpu_product(q, path=MFMA)
+    assert np.array_equal(Yg, Yo)
+    # block-row 1 stores block-column 2 twice: the matrix-core path is not available, AUTO takes the wavefront kernels
+    rng = np.random.default_rng(34)
+    ptr = np.array([0, 2, 5, 5, 6], dtype=np.int32)
+    idx = np.array([0, 3, 2, 1, 2, 3], dtype=np.int32)
+    data = rng.integers(-3, 4, size=(6, 1, 16)).astype(np.float32)
+    X = rng.integers(-3, 4, size=(20, 64)).astype(np.float32)
+    d = wl.Problem("dup", 20, 64, 4, 1, 16, "f32", "f32", X, data, idx, ptr)
+    Yo, So = oracle_of(oracle_mod, d)
+    Wd = lib.bsr_create(d.n, d.k, d.block_data, d.block_indices, d.index_pointer, dtype="f32")
+    assert lib.bsr_query_path(Wd, 20) == WAVE
+    Yg, _ = gpu_product(d, path=0, W=Wd)
+    assert np.array_equal(Yg, Yo)
+    Xd = to_device(d.X, "f32")
+    Y = torch.zeros((20, 4), device="cuda")
+    assert lib.load_library().bsr_spmm_ex(Wd.handle, 20, Xd.data_ptr(), Y.data_ptr(), 0, MFMA,
+                                          torch.cuda.current_stream().cuda_stream) == 9   # BSR_ERR_UNSUPPORTED
+
+
 @pytest.mark.parametrize("u", ["", "a=4", "a=8", "a=16", "a=6,b=1", "a=10,b=2", "b=4", "a=14,b=8"])
 def test_thin_mfma_path(oracle_mod, monkeypatch, u):
     """16x1 fp32 blocks on the matrix-core path with a transposed copy of X in lent scratch (variant 1), then
