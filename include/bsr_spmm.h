@@ -166,7 +166,8 @@ bsr_status bsr_set_scratch(bsr_matrix* W, void* scratch_dev, size_t bytes);
 /*
  * As bsr_spmm() with the kernel family fixed.  BSR_PATH_MFMA needs bs_r and bs_c in {16, 32, 64};
  * or bs_r and bs_c in {8, 16} with n and k multiples of 16 (the blocks are grouped into 16x16
- * tiles); or the thin shape bs_c == 1 with bs_r == 16 and fp32; otherwise BSR_ERR_UNSUPPORTED.
+ * tiles); or the thin shape bs_c == 1 with bs_r == 16 and fp32; or its transpose, bs_r == 1 with bs_c == 16,
+ * fp32, fp32 output and no block stored twice; otherwise BSR_ERR_UNSUPPORTED.
  * BSR_PATH_WAVE takes any shape.
  */
 bsr_status bsr_spmm_ex(const bsr_matrix* W, int64_t m, const void* X_dev, void* Y_dev,
