@@ -9,7 +9,7 @@
 //     D[i][p] = sum_a X[i][16 j + a] * block_data[p][0][a]          (16 rows of X) x (16 a) x (16 blocks p)
 // which is one 16x16x16 product per 16 blocks, and D[i][p] is a term of Y[i][block-row of p].  The terms are
 // added where they belong in LDS: a workgroup owns 16 rows of X and a range of 256 output columns, each of
-// its 8 wavefronts keeps a private 16 x 256 tile of partial sums there, takes every 8th block-column, and
+// its 8 wavefronts keeps a private 16 x 256 tile of partial sums there, takes an eighth of the block-columns, and
 // adds its D values into its own tile (LDS add instructions on addresses that differ within an instruction;
 // a wavefront's LDS operations execute in order, so the order of additions is fixed and runs repeat bit for
 // bit).  At the end the 8 tiles are summed in fixed order and stored as whole rows of 1 KiB.
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(kThreads) void bsr_wide16_f32(const float* __restri
     // where this lane's four results of a chunk go: rows 4*kk + jj of the tile, column = the block's block-row
     unsigned char* const t_at = tile + (4 * kk) * (kTS * 4);
 
-    // The wavefront's chunks (block-columns wave, wave + 8, ... of this range, their pairs 16 at a time) are
+    // The wavefront's chunks (its share of this range's block-columns, their pairs 16 at a time) are
     // listed in the plan; their descriptors {block-column, first pair, pairs} come 64 at a time, one per lane.
     const int lst = __builtin_amdgcn_readfirstlane(chunk_ptr[q * kWv + wave]);
     const int lend = __builtin_amdgcn_readfirstlane(chunk_ptr[q * kWv + wave + 1]);
@@ -232,7 +232,7 @@ void build_wide_plan(bsr_matrix* W, const int32_t* ptr, const int32_t* idx, size
             pairs[2 * (size_t)o] = p * 64;
             pairs[2 * (size_t)o + 1] = r;
         }
-    // Chunk lists: for every range q and wavefront w, the runs (block-column j = w, w + 8, ...; the pairs of j
+    // Chunk lists: for every range q and wavefront w, the runs of its block-columns (the pairs of block-column j
     // whose block-rows fall into the range) cut into chunks of at most 16 pairs: {j, first pair, pairs, 0}.
     std::vector<int32_t> chunks, chunk_ptr;
     std::vector<int32_t> cur(first.begin(), first.end() - 1);    // per block-column: first pair not yet listed
@@ -244,9 +244,27 @@ void build_wide_plan(bsr_matrix* W, const int32_t* ptr, const int32_t* idx, size
             while (o < first[j + 1] && pairs[2 * (size_t)o + 1] < (qq + 1) * kQW) ++o;
             lim[j] = o;
         }
+        // The block-columns go to the wavefronts so that all get about the same number of chunks: longest run
+        // first, each to the wavefront with the fewest chunks so far (the workgroup waits for its slowest).
+        std::vector<int32_t> order;
+        for (int j = 0; j < C; ++j)
+            if (lim[j] > cur[j]) order.push_back(j);
+        std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+            return (lim[x] - cur[x] + 15) / 16 > (lim[y] - cur[y] + 15) / 16;
+        });
+        std::vector<int32_t> mine[kWv];
+        int64_t load[kWv] = {};
+        for (const int32_t j : order) {
+            int w = 0;
+            for (int v = 1; v < kWv; ++v)
+                if (load[v] < load[w]) w = v;
+            mine[w].push_back(j);
+            load[w] += (lim[j] - cur[j] + 15) / 16;
+        }
         for (int w = 0; w < kWv; ++w) {
             chunk_ptr.push_back((int32_t)(chunks.size() / 4));
-            for (int j = w; j < C; j += kWv)
+            std::sort(mine[w].begin(), mine[w].end());           // ascending block-column: neighbouring pieces of X in turn
+            for (const int32_t j : mine[w])
                 for (int32_t e = cur[j]; e < lim[j]; e += 16) {
                     chunks.push_back(j);
                     chunks.push_back(e);
