@@ -250,14 +250,21 @@ bsr_status bsr_create(bsr_matrix** out, int64_t n, int64_t k, int32_t bs_r, int3
     (void)hipGetLastError();
 
     // ---- plan: block-rows by stored-block count, longest first (stable, so equal rows keep
-    //      their natural order and neighbouring rows stay neighbours in the launch) ----
+    //      their natural order and neighbouring rows stay neighbours in the launch, unless said otherwise below) ----
     std::vector<int32_t> cnt((size_t)R);
     for (int64_t r = 0; r < R; ++r) cnt[(size_t)r] = index_pointer_host[r + 1] - index_pointer_host[r];
     const size_t order_words = (((size_t)R * 4 + 255) & ~(size_t)255) / 4;   // row_order, padded to 256 B
     W->staging.assign(order_words + (size_t)R * kRowDescWords + 64, 0);
     std::iota(W->staging.begin(), W->staging.begin() + R, 0);
-    std::stable_sort(W->staging.begin(), W->staging.begin() + R,
-                     [&](int32_t a, int32_t b) { return cnt[(size_t)a] > cnt[(size_t)b]; });
+    // Block-rows whose outputs fill whole 128-byte lines of Y by themselves have nothing to gain from their
+    // neighbours in the launch; among equally long ones they go by their first block-column instead, so that
+    // rows that read the same tiles of X run at about the same time and find them in their XCD's L2.
+    const bool by_column = (size_t)bs_r * (dtype == BSR_F32 ? 4 : 2) >= 128;
+    std::stable_sort(W->staging.begin(), W->staging.begin() + R, [&](int32_t a, int32_t b) {
+        if (cnt[(size_t)a] != cnt[(size_t)b]) return cnt[(size_t)a] > cnt[(size_t)b];
+        if (!by_column || cnt[(size_t)a] == 0) return false;
+        return block_indices_host[index_pointer_host[a]] < block_indices_host[index_pointer_host[b]];
+    });
     // Row descriptors, in slot order: everything a workgroup needs to start on its block-row in
     // ONE read (block-row, first stored block, block count, the first block-columns), instead of
     // the dependent chain row_order -> index_pointer -> block_indices.
