@@ -1,6 +1,7 @@
 // Matrix-core kernel for wide blocks of one row: bs_r = 1, bs_c = 16, fp32 -- the shape a thin (16x1) W has
 // once it is transposed, i.e. the sibling product Z = G*W of a layer with thin blocks run through the handle
-// of W^T (here, as everywhere in the library, the product is Y = X * W^T of the handle's own W).
+// of W^T (here, as everywhere in the library, the product is Y = X * W^T of the handle's own W; the paper's
+// Introduction has the sparse layers trained as well as run, and training needs the product with W itself).
 //
 // A 1x16 block couples 16 columns of X with ONE column of Y, so in the definition's form (per output column:
 // a sum over its stored blocks) no two output columns share a reduction index and a matrix-core tile would
