@@ -82,9 +82,13 @@ __global__ __launch_bounds__(768) void bsr_mfma_stripe16(const T* __restrict__ X
         for (int q = 0; q < KP; ++q) e[q] = pairs[qb + q];
 #pragma unroll
         for (int q = 0; q < KP; ++q) {
-            const unsigned off = (unsigned)(second ? e[q].y : e[q].x) + lane_w;
+            // the entry is the same for the whole wavefront: its four words as scalars, so that each choice between
+            // the pair's two blocks is one select (picked out of the vector by a lane-dependent index it was four)
+            const int o1 = __builtin_amdgcn_readfirstlane(e[q].x), o2 = __builtin_amdgcn_readfirstlane(e[q].y);
+            const int c1 = __builtin_amdgcn_readfirstlane(e[q].z) * PS, c2 = __builtin_amdgcn_readfirstlane(e[q].w) * PS;
+            const unsigned off = (unsigned)(second ? o2 : o1) + lane_w;
             wreg[buf][q] = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)off, 0, 0);
-            xoff[buf][q] = (unsigned)(second ? e[q].w : e[q].z) * PS + lane_x;
+            xoff[buf][q] = (unsigned)(second ? c2 : c1) + lane_x;
         }
     };
 
